@@ -1,0 +1,186 @@
+"""Seeded synthetic workloads for the Stem prefill hot path.
+
+This module only *describes* workloads and draws their random tensors.  It holds
+none of the method's arithmetic (no pooling, metric, schedule, selection or
+attention): both the CPU oracle's tests and the HIP path's tests/bench feed from
+the tensors produced here, and neither side's code lives here.
+
+The tensors stand in for the paper's real workloads (long prompts run through
+Llama-3.1-8B-Instruct / Qwen3-8B, Experimental Settings section): they take the
+attention shapes of those models (32/8 and 28/4 GQA heads, head_dim 128), the
+paper's block size B=128 and its 16K-128K length range, and add the structure a
+block-sparse selector reacts to: an attention sink at the first token of every
+sequence, a short-range (local) query/key correlation, and a few key blocks
+whose value rows are large ("high-energy" blocks the Output-Aware Metric is
+meant to keep, Output-Aware Metric section).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Dict, List, Sequence, Tuple
+
+import torch
+
+SHARED_QUERY_COMPONENT = 0.125  # weight of the per-KV-group direction a_g added to every query
+SINK_GAIN = 4.0                 # first key of a sequence = SINK_GAIN * mean query of its group
+LOCAL_BIAS_GAIN = 0.5           # K_j += LOCAL_BIAS_GAIN * mean_h Q_{j+LOCAL_BIAS_OFFSET}
+LOCAL_BIAS_OFFSET = 8
+V_OUTLIER_GAIN = 4.0            # value rows of the outlier blocks are multiplied by this
+
+
+@dataclass(frozen=True)
+class Workload:
+    """One attention layer's worth of synthetic prefill input plus Stem's knobs.
+
+    k_start_blocks is the block-level start budget per packed sequence (the
+    paper states k_start directly in blocks, Implementation Details); mu = 1.0
+    turns the decay schedule into the uniform top-k control of the ablation.
+    """
+    name: str
+    seed: int
+    num_q_heads: int
+    num_kv_heads: int
+    seq_lens: Tuple[int, ...]
+    block_size: int
+    k_start_blocks: Tuple[int, ...]
+    n_sink: int
+    n_local: int
+    outlier_blocks: Tuple[int, ...]          # per sequence, per KV head
+    head_dim: int = 128
+    mu: float = 0.7
+    beta: float = 0.2
+    route_scale: float = 1.0
+    local_bias: bool = True
+    target_density: float = 0.0              # the density the budget was solved for (0: not solved)
+    k_min: int = 0                           # minimum total budget on top of the forced windows
+    note: str = ""
+
+    @property
+    def total_tokens(self) -> int:
+        return sum(self.seq_lens)
+
+    @property
+    def cu_seqlens(self) -> List[int]:
+        out = [0]
+        for n in self.seq_lens:
+            out.append(out[-1] + n)
+        return out
+
+    @property
+    def blocks_per_seq(self) -> List[int]:
+        b = self.block_size
+        return [(n + b - 1) // b for n in self.seq_lens]
+
+    @property
+    def total_rows(self) -> int:
+        return sum(self.blocks_per_seq)
+
+    @property
+    def admissible_blocks(self) -> int:
+        """Causal (query block, key block) pairs per head: the density denominator."""
+        return sum(n * (n + 1) // 2 for n in self.blocks_per_seq)
+
+    @property
+    def softmax_scale(self) -> float:
+        return float(self.head_dim) ** -0.5
+
+
+def _llama(name, seed, seq_lens, ks, outliers, **kw) -> Workload:
+    base = dict(num_q_heads=32, num_kv_heads=8, block_size=128, n_sink=2, n_local=2)
+    base.update(kw)
+    return Workload(name=name, seed=seed, seq_lens=tuple(seq_lens), k_start_blocks=tuple(ks),
+                    outlier_blocks=tuple(outliers), **base)
+
+
+# --- the five benchmark configurations --------------------------------------------------------
+# k_start_blocks are the smallest start budgets whose block density (retained / admissible causal
+# blocks) reaches target_density under the decay schedule with mu = 0.7; the CPU tests re-derive
+# them with the oracle's schedule, so a change to either side shows up there.
+
+TINY_4K = Workload(
+    name="tiny_4k", seed=0, num_q_heads=1, num_kv_heads=1, seq_lens=(4096,), block_size=64,
+    k_start_blocks=(12,), n_sink=2, n_local=1, outlier_blocks=(4,), local_bias=False,
+    target_density=0.25, note="single head, 64 blocks of 64; the oracle runs it whole in seconds")
+
+LLAMA_32K = _llama("llama8b_32k", 1, (32768,), (25,), (16,), target_density=0.15)
+
+LLAMA_128K = _llama("llama8b_128k", 2, (131072,), (51,), (64,), target_density=0.08,
+                    note="headline benchmark layer")
+
+_SWEEP = dict(num_q_heads=28, num_kv_heads=4)
+SWEEP_64K = {
+    "d100": _llama("gqa7_64k_d100", 3, (65536,), (512,), (64,), mu=1.0, target_density=1.0, **_SWEEP),
+    "d50": _llama("gqa7_64k_d50", 3, (65536,), (188,), (64,), target_density=0.50, **_SWEEP),
+    "d20": _llama("gqa7_64k_d20", 3, (65536,), (66,), (64,), target_density=0.20, **_SWEEP),
+    "d10": _llama("gqa7_64k_d10", 3, (65536,), (32,), (64,), target_density=0.10, **_SWEEP),
+    "d5": _llama("gqa7_64k_d5", 3, (65536,), (16,), (64,), target_density=0.05, **_SWEEP),
+}
+
+PACKED_128K = _llama("packed_varlen_128k", 4, (8192, 16384, 32768, 73728), (4, 8, 16, 36),
+                     (4, 8, 16, 36), target_density=0.10,
+                     note="k_start = n_blocks/16 per sequence; budget restarts at every sequence")
+
+BENCHMARK_CONFIGS: Dict[str, Workload] = {
+    w.name: w for w in [TINY_4K, LLAMA_32K, LLAMA_128K, *SWEEP_64K.values(), PACKED_128K]
+}
+
+
+def small(name: str = "small", *, seed: int = 11, num_q_heads: int = 4, num_kv_heads: int = 2,
+          seq_lens: Sequence[int] = (640,), block_size: int = 64, k_start: Sequence[int] = (5,),
+          n_sink: int = 1, n_local: int = 1, outliers: Sequence[int] = (2,), **kw) -> Workload:
+    """A test-sized workload with the same structure as the benchmark ones."""
+    return Workload(name=name, seed=seed, num_q_heads=num_q_heads, num_kv_heads=num_kv_heads,
+                    seq_lens=tuple(seq_lens), block_size=block_size, k_start_blocks=tuple(k_start),
+                    n_sink=n_sink, n_local=n_local, outlier_blocks=tuple(outliers), **kw)
+
+
+def generate(w: Workload) -> Dict[str, torch.Tensor]:
+    """Draw Q [T,Hq,d], K and V [T,Hkv,d] as bf16 CPU tensors (round-to-nearest-even from fp32).
+
+    Draw order from one torch CPU generator seeded with w.seed: Q, K, V, the per-KV-group shared
+    query direction, then the outlier block choices (sequence-major, KV-head-minor).
+    """
+    g = torch.Generator(device="cpu").manual_seed(w.seed)
+    T, Hq, Hkv, d, B = w.total_tokens, w.num_q_heads, w.num_kv_heads, w.head_dim, w.block_size
+    G = Hq // Hkv
+    q = torch.randn(T, Hq, d, generator=g, dtype=torch.float32)
+    k = torch.randn(T, Hkv, d, generator=g, dtype=torch.float32)
+    v = torch.randn(T, Hkv, d, generator=g, dtype=torch.float32)
+
+    # Shared query direction per KV group: gives the group's queries a common mean for the sink
+    # key to align with.
+    a = torch.randn(Hkv, d, generator=g, dtype=torch.float32)
+    qg = q.view(T, Hkv, G, d)
+    qg += SHARED_QUERY_COMPONENT * a[None, :, None, :]
+    q_group_mean = qg.mean(dim=2)                                     # [T, Hkv, d]
+
+    cu = w.cu_seqlens
+    for s, n in enumerate(w.seq_lens):
+        lo, hi = cu[s], cu[s + 1]
+        k[lo] = SINK_GAIN * q_group_mean[lo:hi].mean(dim=0)
+        if w.local_bias and n > LOCAL_BIAS_OFFSET:
+            k[lo:hi - LOCAL_BIAS_OFFSET] += LOCAL_BIAS_GAIN * q_group_mean[lo + LOCAL_BIAS_OFFSET:hi]
+    del q_group_mean
+
+    outlier_ids: List[List[List[int]]] = []
+    for s, nb in enumerate(w.blocks_per_seq):
+        per_head = []
+        for h in range(Hkv):
+            cnt = min(w.outlier_blocks[s], nb)
+            blocks = torch.randperm(nb, generator=g)[:cnt].tolist()
+            for b in blocks:
+                lo = cu[s] + b * B
+                hi = min(cu[s] + (b + 1) * B, cu[s + 1])
+                v[lo:hi, h] *= V_OUTLIER_GAIN
+            per_head.append(sorted(blocks))
+        outlier_ids.append(per_head)
+
+    return {
+        "q": q.to(torch.bfloat16), "k": k.to(torch.bfloat16), "v": v.to(torch.bfloat16),
+        "outlier_blocks": outlier_ids,
+    }
+
+
+def with_budget(w: Workload, k_start: Sequence[int], mu: float, name_suffix: str) -> Workload:
+    """Same tensors (same seed and shape), different budget schedule."""
+    return replace(w, k_start_blocks=tuple(k_start), mu=mu, name=w.name + name_suffix)
