@@ -1,0 +1,149 @@
+/*
+ * stem.h - C ABI of the MI355X (gfx950) implementation of Stem's block-sparse prefill attention.
+ *
+ * The three stages of the method (Overall Algorithm section, Algorithm 1):
+ *   1. stem_estimate     block-wise pooling of Q, K and of the value magnitude, then the coarse
+ *                        Output-Aware Metric of every causal (query block, key block) pair
+ *                        (Algorithm 1 step 1 and step 3a, Eq. 7);
+ *   2. stem_select       Token Position-Decay top-k(i) of each metric row with the initial and
+ *                        local windows always kept (Eq. 3, Algorithm 1 steps 3b-3c, Implementation
+ *                        Details);
+ *   3. stem_sparse_attn  exact softmax attention over the selected key blocks only
+ *                        (Algorithm 1 step 3d).
+ *
+ * Conventions shared by every entry point
+ *   - Every function returns an int status: STEM_OK (0) or a negative STEM_ERR_* code.  Arguments
+ *     are checked on the host before anything is enqueued; on an error nothing was launched.
+ *   - Pointers are DEVICE pointers unless their name starts with host_.  The caller owns every
+ *     buffer (inputs, outputs, workspace).  The library allocates nothing, keeps no state, does not
+ *     synchronise, and enqueues all work on the caller's stream (`hip_stream` is a hipStream_t; NULL
+ *     is the default stream).  Buffers must stay alive until that work has finished.
+ *   - Q is [T, Hq, d], K and V are [T, Hkv, d], bf16, packed over `batch` sequences whose token
+ *     ranges are host_cu_seqlens[s] .. host_cu_seqlens[s+1].  The last dimension is contiguous;
+ *     token and head strides are given in elements and must be multiples of 8, and base pointers
+ *     must be 16-byte aligned.  Query head h reads KV head h / (Hq / Hkv).
+ *   - A sequence of len tokens has ceil(len / B) blocks; the last block may be partial.  Query-block
+ *     rows of all sequences are numbered consecutively: R = sum of blocks ("rows"), NBmax = the
+ *     longest sequence in blocks.  Key-block indices are 0-based and local to the row's sequence;
+ *     row i of a sequence may use key blocks 0..i.
+ *   - Supported: head_dim 128; block_size 64 or 128; 1 <= batch <= STEM_MAX_BATCH; Hq a multiple
+ *     of Hkv; NBmax <= STEM_MAX_BLOCKS.
+ */
+#ifndef STEM_H
+#define STEM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define STEM_OK                 0
+#define STEM_ERR_INVALID_ARG   (-1)  /* null pointer, bad size, misaligned pointer or stride       */
+#define STEM_ERR_UNSUPPORTED   (-2)  /* a valid request this build has no kernel for               */
+#define STEM_ERR_WORKSPACE     (-3)  /* workspace_bytes smaller than stem_workspace_bytes reports  */
+#define STEM_ERR_HIP           (-4)  /* the HIP runtime refused a launch                           */
+
+#define STEM_MAX_BATCH   64
+#define STEM_MAX_BLOCKS  4096        /* key blocks per sequence (512K tokens at B = 128)           */
+
+typedef struct stem_shape {
+    int32_t num_q_heads;             /* Hq                                                          */
+    int32_t num_kv_heads;            /* Hkv, divides Hq                                             */
+    int32_t head_dim;                /* d = 128                                                     */
+    int32_t block_size;              /* B = 64 or 128 (the paper fixes 128)                         */
+    int32_t batch;                   /* number of packed sequences                                  */
+    const int32_t* host_cu_seqlens;  /* HOST [batch+1], cu[0] = 0, non-decreasing; read during call */
+    int64_t q_stride_token;          /* elements between consecutive tokens of Q (and of O)         */
+    int64_t q_stride_head;           /* elements between consecutive heads of Q (and of O)          */
+    int64_t kv_stride_token;         /* same for K and V (they share strides)                       */
+    int64_t kv_stride_head;
+} stem_shape;
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int stem_version(void);
+
+/* Static, NUL-terminated description of a status code. */
+const char* stem_strerror(int status);
+
+/* R (total query-block rows) and NBmax (blocks of the longest sequence) of a shape. */
+int stem_rows(const stem_shape* shape, int32_t* host_total_rows, int32_t* host_max_blocks);
+
+/* Bytes of device workspace stem_estimate / stem_pool need for this shape.  Layout (fp32):
+ *   q_bar [Hq, R, d] | k_bar [Hkv, R, d] | m_v [Hkv, R]   (each part starts 256-byte aligned). */
+int stem_workspace_bytes(const stem_shape* shape, size_t* host_bytes);
+
+/* Byte offsets of the three workspace parts (for callers that want to look at them). */
+int stem_workspace_layout(const stem_shape* shape, size_t* host_q_bar_offset,
+                          size_t* host_k_bar_offset, size_t* host_m_v_offset);
+
+/*
+ * Token Position-Decay schedule, Eq. 3 in block units, on the host.
+ * For the 0-based row i of a sequence with n blocks and start budget ks = host_k_start_blocks[s]:
+ *     k(i)     = floor( ks - (ks * (1 - mu) / n) * (i + 1) + 1e-9 )
+ *     k_eff(i) = min( i + 1, max( k(i), k_min, |forced(i)| ) )
+ * where forced(i) = first n_sink blocks united with the last n_local causal blocks (diagonal
+ * included).  mu = 1 gives the uniform top-k control.  Writes host_budget[R] and, if not NULL,
+ * the largest entry to *host_kmax.  Requires 0 < mu <= 1, ks >= 0, k_min, n_sink, n_local >= 0.
+ */
+int stem_budget_schedule(const stem_shape* shape, const double* host_k_start_blocks, double mu,
+                         int32_t k_min, int32_t n_sink, int32_t n_local,
+                         int32_t* host_budget, int32_t* host_kmax);
+
+/*
+ * Algorithm 1 step 1: pooled block representations into the workspace (layout above).
+ *   q_bar[h, r, :] = mean over the valid tokens of row r's block of Q[t, h, :]      (fp32)
+ *   k_bar[g, r, :] = the same for K
+ *   m_v[g, r]      = max over the block's valid tokens of ln ||V[t, g, :]||_2  (-inf if all zero)
+ */
+int stem_pool(const stem_shape* shape, const void* q, const void* k, const void* v,
+              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Algorithm 1 step 3a, Eq. 7, from a pooled workspace:
+ *   scores[h, r, j] = route_scale * <q_bar[h, r], k_bar[g, row0(r) + j]> + beta * max(0, m_v[g, row0(r) + j])
+ * for 0 <= j <= i(r); -inf for i(r) < j < NBmax.  scores is fp32 [Hq, R, NBmax].
+ * route_scale = 1 is Eq. 7 as printed; 1/sqrt(d) gives the scaling of Eq. 6.
+ */
+int stem_block_scores(const stem_shape* shape, const void* workspace, size_t workspace_bytes,
+                      float beta, float route_scale, float* scores, void* hip_stream);
+
+/* Stage 1 = stem_pool followed by stem_block_scores.  ad_stride must be 1 (block-mean pooling);
+ * other anti-diagonal strides return STEM_ERR_UNSUPPORTED. */
+int stem_estimate(const stem_shape* shape, const void* q, const void* k, const void* v,
+                  float beta, float route_scale, int32_t ad_stride, float* scores,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Stage 2, Algorithm 1 step 3c with forced windows.  For every head h and row r (local index i):
+ *   k = min(i + 1, max(budget[r], |forced(i)|));
+ *   list = forced(i) united with the k - |forced(i)| best-scoring other causal blocks, equal
+ *          scores going to the lower block index; written ascending.
+ * budget is device int32 [R] (from stem_budget_schedule, copied by the caller).
+ * counts is device int32 [Hq, R]; indices is device int32 [Hq, R, kmax], padded with -1.
+ * kmax is the row pitch of indices.  It must be at least n_sink + n_local (or at least NBmax), so the
+ * forced blocks always fit; a row whose budget exceeds kmax is cut to kmax blocks (k = min(k, kmax)).
+ */
+int stem_select(const stem_shape* shape, const float* scores, const int32_t* budget,
+                int32_t n_sink, int32_t n_local, int32_t* counts, int32_t* indices, int32_t kmax,
+                void* hip_stream);
+
+/*
+ * Stage 3, Algorithm 1 step 3d: for every head h, row r and valid query token t of the row's block
+ *   out[t, h, :] = sum_u softmax_u( softmax_scale * <Q[t,h], K[u,g]> ) V[u,g]
+ * over the tokens u <= t of the key blocks indices[h, r, 0 .. counts[h,r]).  bf16 inputs, bf16 MFMA
+ * products with fp32 accumulation, fp32 softmax, bf16 output with Q's strides.  softmax_scale > 0.
+ * lse (device fp32 [Hq, T], may be NULL) receives log sum_u exp(softmax_scale * <Q,K>) per query.
+ * Any list is accepted, not only stem_select's, provided each row's list is ascending, causal
+ * (entries <= i) and holds the diagonal block i.  Lists are not validated: entries outside 0..i
+ * are skipped (never an out-of-bounds access); a row with no usable entry yields zeros.
+ */
+int stem_sparse_attn(const stem_shape* shape, const void* q, const void* k, const void* v,
+                     const int32_t* counts, const int32_t* indices, int32_t kmax,
+                     float softmax_scale, void* out, float* lse, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STEM_H */

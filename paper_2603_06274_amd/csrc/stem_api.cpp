@@ -1,0 +1,239 @@
+// Host side of libstem_hip: argument checks, shape bookkeeping, the Token Position-Decay schedule
+// helper (Eq. 3) and the dispatch of the four kernels.  No allocation, no synchronisation.
+#include <cmath>
+#include <cstring>
+
+#include "stem_common.h"
+
+namespace stem {
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int make_problem(const stem_shape* s, Problem* out) {
+    if (!s || !out || !s->host_cu_seqlens) return STEM_ERR_INVALID_ARG;
+    if (s->num_q_heads <= 0 || s->num_kv_heads <= 0 || s->num_q_heads % s->num_kv_heads)
+        return STEM_ERR_INVALID_ARG;
+    if (s->batch < 1 || s->batch > STEM_MAX_BATCH) return STEM_ERR_INVALID_ARG;
+    if (s->head_dim <= 0 || s->block_size <= 0) return STEM_ERR_INVALID_ARG;
+    if (s->head_dim != kHeadDim) return STEM_ERR_UNSUPPORTED;
+    if (s->block_size != 64 && s->block_size != 128) return STEM_ERR_UNSUPPORTED;
+    if (s->q_stride_head < kHeadDim || s->kv_stride_head < kHeadDim) return STEM_ERR_INVALID_ARG;
+    if (s->q_stride_token < kHeadDim || s->kv_stride_token < kHeadDim) return STEM_ERR_INVALID_ARG;
+    if ((s->q_stride_head | s->q_stride_token | s->kv_stride_head | s->kv_stride_token) & 7)
+        return STEM_ERR_INVALID_ARG;
+    Problem p;
+    std::memset(&p, 0, sizeof(p));
+    p.Hq = s->num_q_heads;
+    p.Hkv = s->num_kv_heads;
+    p.G = p.Hq / p.Hkv;
+    p.B = s->block_size;
+    p.batch = s->batch;
+    p.q_st = s->q_stride_token;
+    p.q_sh = s->q_stride_head;
+    p.kv_st = s->kv_stride_token;
+    p.kv_sh = s->kv_stride_head;
+    if (s->host_cu_seqlens[0] != 0) return STEM_ERR_INVALID_ARG;
+    p.seq.batch = p.batch;
+    int64_t rows = 0;
+    int32_t nbmax = 0;
+    for (int i = 0; i < p.batch; ++i) {
+        int64_t lo = s->host_cu_seqlens[i], hi = s->host_cu_seqlens[i + 1];
+        if (hi < lo) return STEM_ERR_INVALID_ARG;
+        int64_t nb = (hi - lo + p.B - 1) / p.B;
+        if (nb > STEM_MAX_BLOCKS) return STEM_ERR_UNSUPPORTED;
+        p.seq.tok_start[i] = (int32_t)lo;
+        p.seq.row_start[i] = (int32_t)rows;
+        rows += nb;
+        if (nb > nbmax) nbmax = (int32_t)nb;
+    }
+    if (rows > (int64_t)1 << 24) return STEM_ERR_UNSUPPORTED;
+    p.seq.tok_start[p.batch] = s->host_cu_seqlens[p.batch];
+    p.seq.row_start[p.batch] = (int32_t)rows;
+    for (int i = p.batch + 1; i <= STEM_MAX_BATCH; ++i) {
+        p.seq.tok_start[i] = p.seq.tok_start[p.batch];
+        p.seq.row_start[i] = p.seq.row_start[p.batch];
+    }
+    p.T = s->host_cu_seqlens[p.batch];
+    p.R = (int32_t)rows;
+    p.NBmax = nbmax;
+    *out = p;
+    return STEM_OK;
+}
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+WorkspaceLayout workspace_layout(const Problem& p) {
+    WorkspaceLayout w;
+    w.q_bar = 0;
+    w.k_bar = align256(w.q_bar + sizeof(float) * (size_t)p.Hq * p.R * kHeadDim);
+    w.m_v = align256(w.k_bar + sizeof(float) * (size_t)p.Hkv * p.R * kHeadDim);
+    w.total = align256(w.m_v + sizeof(float) * (size_t)p.Hkv * p.R);
+    if (w.total == 0) w.total = 256;
+    return w;
+}
+
+}  // namespace stem
+
+using namespace stem;
+
+extern "C" {
+
+int stem_version(void) { return 100; }
+
+const char* stem_strerror(int status) {
+    switch (status) {
+        case STEM_OK: return "ok";
+        case STEM_ERR_INVALID_ARG: return "invalid argument";
+        case STEM_ERR_UNSUPPORTED: return "unsupported shape or option";
+        case STEM_ERR_WORKSPACE: return "workspace too small";
+        case STEM_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int stem_rows(const stem_shape* shape, int32_t* host_total_rows, int32_t* host_max_blocks) {
+    Problem p;
+    int st = make_problem(shape, &p);
+    if (st != STEM_OK) return st;
+    if (host_total_rows) *host_total_rows = p.R;
+    if (host_max_blocks) *host_max_blocks = p.NBmax;
+    return STEM_OK;
+}
+
+int stem_workspace_bytes(const stem_shape* shape, size_t* host_bytes) {
+    Problem p;
+    int st = make_problem(shape, &p);
+    if (st != STEM_OK) return st;
+    if (!host_bytes) return STEM_ERR_INVALID_ARG;
+    *host_bytes = workspace_layout(p).total;
+    return STEM_OK;
+}
+
+int stem_workspace_layout(const stem_shape* shape, size_t* host_q_bar_offset,
+                          size_t* host_k_bar_offset, size_t* host_m_v_offset) {
+    Problem p;
+    int st = make_problem(shape, &p);
+    if (st != STEM_OK) return st;
+    WorkspaceLayout w = workspace_layout(p);
+    if (host_q_bar_offset) *host_q_bar_offset = w.q_bar;
+    if (host_k_bar_offset) *host_k_bar_offset = w.k_bar;
+    if (host_m_v_offset) *host_m_v_offset = w.m_v;
+    return STEM_OK;
+}
+
+int stem_budget_schedule(const stem_shape* shape, const double* host_k_start_blocks, double mu,
+                         int32_t k_min, int32_t n_sink, int32_t n_local, int32_t* host_budget,
+                         int32_t* host_kmax) {
+    Problem p;
+    int st = make_problem(shape, &p);
+    if (st != STEM_OK) return st;
+    if (!host_k_start_blocks || !host_budget) return STEM_ERR_INVALID_ARG;
+    if (!(mu > 0.0) || mu > 1.0 || k_min < 0 || n_sink < 0 || n_local < 0) return STEM_ERR_INVALID_ARG;
+    for (int s = 0; s < p.batch; ++s)
+        if (!(host_k_start_blocks[s] >= 0.0) || host_k_start_blocks[s] > 1e9) return STEM_ERR_INVALID_ARG;
+    int32_t kmax = 0;
+    for (int s = 0; s < p.batch; ++s) {
+        const int32_t n = p.seq.row_start[s + 1] - p.seq.row_start[s];
+        const double ks = host_k_start_blocks[s];
+        // per-row decrement of Eq. 3; volatile keeps the compiler from contracting the
+        // multiply-subtract below into one fused operation
+        volatile double step = n > 0 ? (ks * (1.0 - mu)) / (double)n : 0.0;
+        for (int32_t i = 0; i < n; ++i) {
+            volatile double dec = step * (double)(i + 1);
+            int64_t k = (int64_t)std::floor(ks - dec + 1e-9);
+            const int32_t head = n_sink < i + 1 ? n_sink : i + 1;             // blocks 0..head-1
+            const int32_t tail_lo = i - n_local + 1 > head ? i - n_local + 1 : head;
+            const int64_t forced = head + (i + 1 - tail_lo);
+            if (k < k_min) k = k_min;
+            if (k < forced) k = forced;
+            if (k > i + 1) k = i + 1;
+            host_budget[p.seq.row_start[s] + i] = (int32_t)k;
+            if (k > kmax) kmax = (int32_t)k;
+        }
+    }
+    if (host_kmax) *host_kmax = kmax;
+    return STEM_OK;
+}
+
+static int check_qkv(const void* q, const void* k, const void* v) {
+    if (!q || !k || !v) return STEM_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return STEM_ERR_INVALID_ARG;
+    return STEM_OK;
+}
+
+int stem_pool(const stem_shape* shape, const void* q, const void* k, const void* v, void* workspace,
+              size_t workspace_bytes, void* hip_stream) {
+    Problem p;
+    int st = make_problem(shape, &p);
+    if (st != STEM_OK) return st;
+    if ((st = check_qkv(q, k, v)) != STEM_OK) return st;
+    if (!workspace || !aligned16(workspace)) return STEM_ERR_INVALID_ARG;
+    WorkspaceLayout w = workspace_layout(p);
+    if (workspace_bytes < w.total) return STEM_ERR_WORKSPACE;
+    if (p.R == 0) return STEM_OK;
+    char* ws = static_cast<char*>(workspace);
+    return launch_pool(p, q, k, v, reinterpret_cast<float*>(ws + w.q_bar),
+                       reinterpret_cast<float*>(ws + w.k_bar), reinterpret_cast<float*>(ws + w.m_v),
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+int stem_block_scores(const stem_shape* shape, const void* workspace, size_t workspace_bytes,
+                      float beta, float route_scale, float* scores, void* hip_stream) {
+    Problem p;
+    int st = make_problem(shape, &p);
+    if (st != STEM_OK) return st;
+    if (!workspace || !aligned16(workspace) || !scores || !aligned16(scores)) return STEM_ERR_INVALID_ARG;
+    if (!std::isfinite(beta) || !std::isfinite(route_scale)) return STEM_ERR_INVALID_ARG;
+    WorkspaceLayout w = workspace_layout(p);
+    if (workspace_bytes < w.total) return STEM_ERR_WORKSPACE;
+    if (p.R == 0) return STEM_OK;
+    const char* ws = static_cast<const char*>(workspace);
+    return launch_block_scores(p, reinterpret_cast<const float*>(ws + w.q_bar),
+                               reinterpret_cast<const float*>(ws + w.k_bar),
+                               reinterpret_cast<const float*>(ws + w.m_v), beta, route_scale, scores,
+                               static_cast<hipStream_t>(hip_stream));
+}
+
+int stem_estimate(const stem_shape* shape, const void* q, const void* k, const void* v, float beta,
+                  float route_scale, int32_t ad_stride, float* scores, void* workspace,
+                  size_t workspace_bytes, void* hip_stream) {
+    if (ad_stride < 1) return STEM_ERR_INVALID_ARG;
+    if (!scores || !aligned16(scores)) return STEM_ERR_INVALID_ARG;
+    if (!std::isfinite(beta) || !std::isfinite(route_scale)) return STEM_ERR_INVALID_ARG;
+    Problem p;
+    int st = make_problem(shape, &p);
+    if (st != STEM_OK) return st;
+    if (ad_stride != 1) return STEM_ERR_UNSUPPORTED;
+    st = stem_pool(shape, q, k, v, workspace, workspace_bytes, hip_stream);
+    if (st != STEM_OK) return st;
+    return stem_block_scores(shape, workspace, workspace_bytes, beta, route_scale, scores, hip_stream);
+}
+
+int stem_select(const stem_shape* shape, const float* scores, const int32_t* budget, int32_t n_sink,
+                int32_t n_local, int32_t* counts, int32_t* indices, int32_t kmax, void* hip_stream) {
+    Problem p;
+    int st = make_problem(shape, &p);
+    if (st != STEM_OK) return st;
+    if (!scores || !budget || !counts || !indices) return STEM_ERR_INVALID_ARG;
+    if (n_sink < 0 || n_local < 0 || kmax < 1) return STEM_ERR_INVALID_ARG;
+    if ((int64_t)kmax < (int64_t)n_sink + n_local && kmax < p.NBmax) return STEM_ERR_INVALID_ARG;
+    if (p.R == 0) return STEM_OK;
+    return launch_select(p, scores, budget, n_sink, n_local, counts, indices, kmax,
+                         static_cast<hipStream_t>(hip_stream));
+}
+
+int stem_sparse_attn(const stem_shape* shape, const void* q, const void* k, const void* v,
+                     const int32_t* counts, const int32_t* indices, int32_t kmax,
+                     float softmax_scale, void* out, float* lse, void* hip_stream) {
+    Problem p;
+    int st = make_problem(shape, &p);
+    if (st != STEM_OK) return st;
+    if ((st = check_qkv(q, k, v)) != STEM_OK) return st;
+    if (!counts || !indices || !out || !aligned16(out) || kmax < 1) return STEM_ERR_INVALID_ARG;
+    if (!std::isfinite(softmax_scale) || !(softmax_scale > 0.f)) return STEM_ERR_INVALID_ARG;
+    if (p.R == 0) return STEM_OK;
+    return launch_sparse_attn(p, q, k, v, counts, indices, kmax, softmax_scale, out, lse,
+                              static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

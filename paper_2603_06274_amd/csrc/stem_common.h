@@ -1,0 +1,63 @@
+// Internal declarations shared by the host API and the gfx950 kernels of libstem_hip.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "stem.h"
+
+namespace stem {
+
+constexpr int kHeadDim = 128;
+
+// Packed-sequence table, passed to kernels by value (no device-side cu_seqlens read, no sync).
+struct SeqTable {
+    int32_t batch;
+    int32_t tok_start[STEM_MAX_BATCH + 1];   // cu_seqlens
+    int32_t row_start[STEM_MAX_BATCH + 1];   // prefix sums of blocks per sequence
+};
+
+// Everything the host derives from a stem_shape.
+struct Problem {
+    int32_t Hq, Hkv, G, B, batch;
+    int32_t T, R, NBmax;
+    int64_t q_st, q_sh, kv_st, kv_sh;
+    SeqTable seq;
+};
+
+int make_problem(const stem_shape* shape, Problem* out);
+
+struct WorkspaceLayout {
+    size_t q_bar, k_bar, m_v, total;
+};
+WorkspaceLayout workspace_layout(const Problem& p);
+
+// Kernel launchers (one per translation unit); each returns a STEM_* status.
+int launch_pool(const Problem& p, const void* q, const void* k, const void* v, float* q_bar,
+                float* k_bar, float* m_v, hipStream_t stream);
+int launch_block_scores(const Problem& p, const float* q_bar, const float* k_bar, const float* m_v,
+                        float beta, float route_scale, float* scores, hipStream_t stream);
+int launch_select(const Problem& p, const float* scores, const int32_t* budget, int32_t n_sink,
+                  int32_t n_local, int32_t* counts, int32_t* indices, int32_t kmax,
+                  hipStream_t stream);
+int launch_sparse_attn(const Problem& p, const void* q, const void* k, const void* v,
+                       const int32_t* counts, const int32_t* indices, int32_t kmax,
+                       float softmax_scale, void* out, float* lse, hipStream_t stream);
+
+inline int check_launch() {
+    return hipGetLastError() == hipSuccess ? STEM_OK : STEM_ERR_HIP;
+}
+
+#if defined(__HIPCC__)
+// Sequence of a global query-block row: the last s with row_start[s] <= r.  Wave-uniform.
+__device__ __forceinline__ int seq_of_row(const SeqTable& t, int r) {
+    int s = 0;
+    for (int x = 1; x < t.batch; ++x) s = (r >= t.row_start[x]) ? x : s;
+    return s;
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+#endif
+
+}  // namespace stem

@@ -1,0 +1,118 @@
+// Stage 1a (Algorithm 1 step 1): block-wise pooling of Q and K and max-pooled value magnitude.
+//
+// Pure HBM stream: every bf16 element of Q, K and V is read exactly once, in 16-byte lane loads
+// that cover one head row (256 B) per 16 lanes.  One workgroup owns one (row, tensor, head) slot:
+// 256 threads = 16 token lanes x 16 column chunks; every thread issues all of its loads (B/16
+// tokens) before it touches the first value, so a workgroup keeps B x 256 B in flight.  Column
+// sums are reduced across the 16 token lanes through LDS in a fixed order (deterministic fp32).
+#include "stem_common.h"
+
+namespace stem {
+
+constexpr int kPoolThreads = 256;
+
+template <int B>
+__global__ __launch_bounds__(kPoolThreads) void pool_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    float* __restrict__ q_bar, float* __restrict__ k_bar, float* __restrict__ m_v, SeqTable seq,
+    int Hq, int Hkv, int R, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh) {
+    constexpr int kTok = B / 16;                       // tokens per thread
+    const int slots = Hq + 2 * Hkv;
+    const int r = blockIdx.x / slots;
+    const int slot = blockIdx.x - r * slots;
+    const int s = seq_of_row(seq, r);
+    const int tok0 = seq.tok_start[s] + (r - seq.row_start[s]) * B;
+    const int n_valid = min(B, seq.tok_start[s + 1] - tok0);
+
+    const uint16_t* src;
+    int64_t st;
+    int kind, head;                                    // 0: Q, 1: K, 2: V
+    if (slot < Hq) {
+        kind = 0; head = slot; src = q + (int64_t)head * q_sh; st = q_st;
+    } else if (slot < Hq + Hkv) {
+        kind = 1; head = slot - Hq; src = k + (int64_t)head * kv_sh; st = kv_st;
+    } else {
+        kind = 2; head = slot - Hq - Hkv; src = v + (int64_t)head * kv_sh; st = kv_st;
+    }
+
+    const int tid = threadIdx.x;
+    const int c = tid & 15;                            // 16-byte chunk of the 128-wide row
+    const int tl = tid >> 4;                           // token lane 0..15
+
+    uint4 raw[kTok];
+#pragma unroll
+    for (int u = 0; u < kTok; ++u) {
+        const int t = tl + 16 * u;
+        raw[u] = make_uint4(0u, 0u, 0u, 0u);
+        if (t < n_valid)
+            raw[u] = *reinterpret_cast<const uint4*>(src + (int64_t)(tok0 + t) * st + c * 8);
+    }
+
+    __shared__ float part[16][kHeadDim + 4];           // [token lane][column]
+    __shared__ float vmax[kPoolThreads / 64];
+
+    if (kind != 2) {
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < kTok; ++u) {
+            acc[0] += bf16_lo(raw[u].x); acc[1] += bf16_hi(raw[u].x);
+            acc[2] += bf16_lo(raw[u].y); acc[3] += bf16_hi(raw[u].y);
+            acc[4] += bf16_lo(raw[u].z); acc[5] += bf16_hi(raw[u].z);
+            acc[6] += bf16_lo(raw[u].w); acc[7] += bf16_hi(raw[u].w);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part[tl][c * 8 + e] = acc[e];
+        __syncthreads();
+        if (tid < kHeadDim) {
+            float sum = 0.f;
+#pragma unroll
+            for (int x = 0; x < 16; ++x) sum += part[x][tid];
+            float* dst = (kind == 0 ? q_bar : k_bar) + ((int64_t)head * R + r) * kHeadDim;
+            dst[tid] = sum / (float)n_valid;
+        }
+    } else {
+        // squared L2 norm of each token row: 8 columns per lane, then across the 16 chunk lanes
+        float best = 0.f;
+#pragma unroll
+        for (int u = 0; u < kTok; ++u) {
+            float x0 = bf16_lo(raw[u].x), x1 = bf16_hi(raw[u].x), x2 = bf16_lo(raw[u].y),
+                  x3 = bf16_hi(raw[u].y), x4 = bf16_lo(raw[u].z), x5 = bf16_hi(raw[u].z),
+                  x6 = bf16_lo(raw[u].w), x7 = bf16_hi(raw[u].w);
+            float ss = ((x0 * x0 + x1 * x1) + (x2 * x2 + x3 * x3)) +
+                       ((x4 * x4 + x5 * x5) + (x6 * x6 + x7 * x7));
+            ss += __shfl_xor(ss, 1);
+            ss += __shfl_xor(ss, 2);
+            ss += __shfl_xor(ss, 4);
+            ss += __shfl_xor(ss, 8);
+            best = fmaxf(best, ss);                    // padded tokens contribute 0
+        }
+        best = fmaxf(best, __shfl_xor(best, 16));
+        best = fmaxf(best, __shfl_xor(best, 32));
+        if ((tid & 63) == 0) vmax[tid >> 6] = best;
+        __syncthreads();
+        if (tid == 0) {
+            float m = fmaxf(fmaxf(vmax[0], vmax[1]), fmaxf(vmax[2], vmax[3]));
+            // max_t ln ||v_t|| = 0.5 ln max_t ||v_t||^2 ; ln 0 = -inf
+            m_v[(int64_t)head * R + r] = 0.5f * logf(m);
+        }
+    }
+}
+
+int launch_pool(const Problem& p, const void* q, const void* k, const void* v, float* q_bar,
+                float* k_bar, float* m_v, hipStream_t stream) {
+    const int64_t blocks = (int64_t)p.R * (p.Hq + 2 * p.Hkv);
+    if (blocks > 0x7fffffff) return STEM_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)blocks), block(kPoolThreads);
+    const uint16_t* qq = static_cast<const uint16_t*>(q);
+    const uint16_t* kk = static_cast<const uint16_t*>(k);
+    const uint16_t* vv = static_cast<const uint16_t*>(v);
+    if (p.B == 128)
+        hipLaunchKernelGGL(pool_kernel<128>, grid, block, 0, stream, qq, kk, vv, q_bar, k_bar, m_v,
+                           p.seq, p.Hq, p.Hkv, p.R, p.q_st, p.q_sh, p.kv_st, p.kv_sh);
+    else
+        hipLaunchKernelGGL(pool_kernel<64>, grid, block, 0, stream, qq, kk, vv, q_bar, k_bar, m_v,
+                           p.seq, p.Hq, p.Hkv, p.R, p.q_st, p.q_sh, p.kv_st, p.kv_sh);
+    return check_launch();
+}
+
+}  // namespace stem

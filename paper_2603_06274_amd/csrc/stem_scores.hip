@@ -1,0 +1,128 @@
+// Stage 1b (Algorithm 1 step 3a, Eq. 7): coarse Output-Aware Metric of every causal block pair,
+//   scores[h, r, j] = route_scale * <q_bar[h, r], k_bar[g, row0 + j]> + beta * max(0, m_v[g, row0 + j]).
+//
+// A small fp32 contraction over d = 128 per head and sequence, lower-triangular in (i, j).  It is
+// kept in full fp32 FMA arithmetic (no bf16 matrix cores) because stage 2 ranks these numbers and
+// must reproduce the ranking of an fp64 evaluation except for genuine near-ties.  64 x 64 output
+// tiles, 4 x 4 per thread, operands staged k-major through LDS; tiles above the diagonal are only
+// filled with -inf.
+#include "stem_common.h"
+
+namespace stem {
+
+constexpr int kTile = 64;
+constexpr int kChunk = 32;                             // slice of d staged per step
+constexpr int kScoreThreads = 256;
+
+struct TileTable {
+    int32_t tile_start[STEM_MAX_BATCH + 1];            // prefix sums of ceil(n_s / kTile)
+};
+
+__global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
+    const float* __restrict__ q_bar, const float* __restrict__ k_bar, const float* __restrict__ m_v,
+    float* __restrict__ scores, SeqTable seq, TileTable tiles, int R, int NBmax, int G, float beta,
+    float route_scale) {
+    // sequence and local row tile of this workgroup
+    int s = 0;
+    for (int x = 1; x < seq.batch; ++x) s = ((int)blockIdx.x >= tiles.tile_start[x]) ? x : s;
+    const int row0 = seq.row_start[s];
+    const int n = seq.row_start[s + 1] - row0;         // blocks of this sequence
+    const int i0 = ((int)blockIdx.x - tiles.tile_start[s]) * kTile;
+    const int j0 = blockIdx.y * kTile;
+    const int h = blockIdx.z;
+    const int g = h / G;
+    const int tid = threadIdx.x;
+    const int ti = tid >> 4, tj = tid & 15;            // 4 rows x 4 columns per thread
+
+    float* out = scores + ((int64_t)h * R + row0) * NBmax;
+    const float neg_inf = -__builtin_huge_valf();
+
+    if (j0 > i0 + kTile - 1) {                         // entirely above the diagonal
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const int i = i0 + ti * 4 + x;
+            if (i >= n) continue;
+#pragma unroll
+            for (int y = 0; y < 4; ++y) {
+                const int j = j0 + tj * 4 + y;
+                if (j < NBmax) out[(int64_t)i * NBmax + j] = neg_inf;
+            }
+        }
+        return;
+    }
+
+    __shared__ float a_s[kChunk][kTile + 4];           // [k][i]
+    __shared__ float b_s[kChunk][kTile + 4];           // [k][j]
+
+    float acc[4][4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int y = 0; y < 4; ++y) acc[x][y] = 0.f;
+
+    const float* a_src = q_bar + ((int64_t)h * R + row0) * kHeadDim;
+    const float* b_src = k_bar + ((int64_t)g * R + row0) * kHeadDim;
+
+    for (int kc = 0; kc < kHeadDim; kc += kChunk) {
+        // 64 rows x 32 floats per operand = 512 float4; two per thread and operand
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = tid + kScoreThreads * u;
+            const int row = idx >> 3, c4 = (idx & 7) * 4;
+            float4 av = make_float4(0.f, 0.f, 0.f, 0.f), bv = av;
+            if (i0 + row < n) av = *reinterpret_cast<const float4*>(a_src + (int64_t)(i0 + row) * kHeadDim + kc + c4);
+            if (j0 + row < n) bv = *reinterpret_cast<const float4*>(b_src + (int64_t)(j0 + row) * kHeadDim + kc + c4);
+            a_s[c4 + 0][row] = av.x; a_s[c4 + 1][row] = av.y; a_s[c4 + 2][row] = av.z; a_s[c4 + 3][row] = av.w;
+            b_s[c4 + 0][row] = bv.x; b_s[c4 + 1][row] = bv.y; b_s[c4 + 2][row] = bv.z; b_s[c4 + 3][row] = bv.w;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < kChunk; ++kk) {
+            const float4 a4 = *reinterpret_cast<const float4*>(&a_s[kk][ti * 4]);
+            const float4 b4 = *reinterpret_cast<const float4*>(&b_s[kk][tj * 4]);
+            const float a[4] = {a4.x, a4.y, a4.z, a4.w};
+            const float b[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+#pragma unroll
+                for (int y = 0; y < 4; ++y) acc[x][y] = fmaf(a[x], b[y], acc[x][y]);
+        }
+        __syncthreads();
+    }
+
+    float mag[4];
+#pragma unroll
+    for (int y = 0; y < 4; ++y) {
+        const int j = j0 + tj * 4 + y;
+        mag[y] = (j < n) ? beta * fmaxf(0.f, m_v[(int64_t)g * R + row0 + j]) : 0.f;
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int i = i0 + ti * 4 + x;
+        if (i >= n) continue;
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+            const int j = j0 + tj * 4 + y;
+            if (j >= NBmax) continue;
+            out[(int64_t)i * NBmax + j] = (j <= i) ? fmaf(route_scale, acc[x][y], mag[y]) : neg_inf;
+        }
+    }
+}
+
+int launch_block_scores(const Problem& p, const float* q_bar, const float* k_bar, const float* m_v,
+                        float beta, float route_scale, float* scores, hipStream_t stream) {
+    TileTable tiles;
+    int total = 0;
+    for (int s = 0; s <= STEM_MAX_BATCH; ++s) {
+        tiles.tile_start[s] = total;
+        if (s < p.batch) total += (p.seq.row_start[s + 1] - p.seq.row_start[s] + kTile - 1) / kTile;
+    }
+    if (total == 0) return STEM_OK;
+    if (p.Hq > 65535) return STEM_ERR_UNSUPPORTED;
+    dim3 grid(total, (p.NBmax + kTile - 1) / kTile, p.Hq), block(kScoreThreads);
+    hipLaunchKernelGGL(block_scores_kernel, grid, block, 0, stream, q_bar, k_bar, m_v, scores, p.seq,
+                       tiles, p.R, p.NBmax, p.G, beta, route_scale);
+    return check_launch();
+}
+
+}  // namespace stem

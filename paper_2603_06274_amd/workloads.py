@@ -157,6 +157,8 @@ def generate(w: Workload) -> Dict[str, torch.Tensor]:
     cu = w.cu_seqlens
     for s, n in enumerate(w.seq_lens):
         lo, hi = cu[s], cu[s + 1]
+        if n == 0:
+            continue
         k[lo] = SINK_GAIN * q_group_mean[lo:hi].mean(dim=0)
         if w.local_bias and n > LOCAL_BIAS_OFFSET:
             k[lo:hi - LOCAL_BIAS_OFFSET] += LOCAL_BIAS_GAIN * q_group_mean[lo + LOCAL_BIAS_OFFSET:hi]

@@ -1,0 +1,170 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle on the same seeded tensors.
+Needs a real MI355X: every test here is marked gpu."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import stem_oracle as so
+from paper_2603_06274_amd import binding as sb
+from paper_2603_06274_amd import workloads as wl
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+SMALL = {
+    # ragged single sequence, GQA 2:1, B = 64
+    "ragged_b64": wl.small("ragged_b64", seed=21, num_q_heads=4, num_kv_heads=2, seq_lens=(1000,),
+                           block_size=64, k_start=(6,), n_sink=1, n_local=1, outliers=(2,)),
+    # packed batch with an empty and a sub-block sequence, GQA 4:1, B = 128
+    "packed_b128": wl.small("packed_b128", seed=22, num_q_heads=8, num_kv_heads=2,
+                            seq_lens=(700, 0, 1536, 130, 50), block_size=128, k_start=(3, 1, 5, 2, 1),
+                            n_sink=1, n_local=2, outliers=(1, 0, 2, 1, 1)),
+    # more than 64 blocks: several score tiles per row, B = 128, MHA
+    "long_b128": wl.small("long_b128", seed=23, num_q_heads=2, num_kv_heads=2, seq_lens=(9000,),
+                          block_size=128, k_start=(12,), n_sink=2, n_local=2, outliers=(6,)),
+    # paper preset windows (4 initial + 4 local, minimum budget) on a short sequence
+    "preset_b128": wl.small("preset_b128", seed=24, num_q_heads=4, num_kv_heads=1, seq_lens=(4096,),
+                            block_size=128, k_start=(6.4,), n_sink=4, n_local=4, outliers=(3,), k_min=10),
+    # no forced windows at all, uniform budget
+    "noforce_b64": wl.small("noforce_b64", seed=25, num_q_heads=2, num_kv_heads=1, seq_lens=(2048, 1024),
+                            block_size=64, k_start=(5, 3), n_sink=0, n_local=1, outliers=(2, 2), mu=1.0),
+}
+
+
+def run_both(w, rows=None, heads=None):
+    say("case", w.name, "seed", w.seed, "T", w.total_tokens, "Hq/Hkv", w.num_q_heads, w.num_kv_heads,
+        "B", w.block_size)
+    data = wl.generate(w)
+    qkv = pu.host_arrays(data)
+    pf = pu.device_prefill(w, data)
+    pf.run()
+    torch.cuda.synchronize()
+    q_bar, k_bar, m_v, scores = pu.oracle_estimate(w, qkv)
+    budget, counts, indices = pu.oracle_select(w, scores)
+    assert pf.budget_host.numpy().tolist() == budget.tolist()
+    pu.check_pooled(pf, q_bar, k_bar, m_v)
+    err = pu.check_scores(pf.scores.cpu().numpy(), scores)
+    same = pu.check_lists(w, pf.counts.cpu().numpy(), pf.indices.cpu().numpy(), counts, indices, scores, say)
+    o_out, o_lse = so.sparse_attention(*qkv, w.cu_seqlens, w.block_size, counts, indices,
+                                       w.softmax_scale, heads=heads, rows=rows)
+    # compare the chained output on rows whose lists agree
+    g_out = pf.out.float().cpu().numpy()
+    g_lse = pf.lse.cpu().numpy()
+    B = w.block_size
+    for (lo, hi, nb, row0) in so.sequence_table(w.cu_seqlens, B):
+        for i in range(nb):
+            for h in range(w.num_q_heads):
+                if not same[h, row0 + i]:
+                    o_out[lo + i * B:min(lo + (i + 1) * B, hi), h] = np.nan
+                    o_lse[h, lo + i * B:min(lo + (i + 1) * B, hi)] = np.nan
+    max_abs, rel_l2 = pu.check_output(g_out, o_out, w.name)
+    m = ~np.isnan(o_lse)
+    assert np.abs(g_lse[m] - o_lse[m]).max() <= 2e-3
+    say("%s: score err %.3g, out max-abs %.4g rel-L2 %.4g" % (w.name, err, max_abs, rel_l2))
+    return pf, data, qkv, (counts, indices)
+
+
+@pytest.mark.parametrize("name", sorted(SMALL))
+def test_small_cases_whole_path(name):
+    run_both(SMALL[name])
+
+
+def test_tiny_4k_whole_path():
+    run_both(wl.TINY_4K)
+
+
+def test_select_is_bit_exact_on_shared_fp32_scores():
+    """Stage 2 alone, on one fp32 score tensor given to both sides (exactly representable in fp64, so
+    no near-tie allowance), with planted exact ties, +-0, and equal rows."""
+    r = np.random.default_rng(31)
+    for (nb, B, Hq, n_sink, n_local, ks) in [(40, 64, 3, 2, 1, 9), (300, 128, 2, 3, 2, 40), (70, 64, 2, 0, 0, 7),
+                                              (1100, 128, 1, 2, 2, 60)]:
+        say("select case nb", nb, "Hq", Hq)
+        cu = [0, nb * B - 5]
+        sc = r.standard_normal((Hq, nb, nb)).astype(np.float32)
+        sc = np.round(sc * 4) / 4                          # many exact ties
+        sc[:, :, 3] = 0.0
+        sc[:, ::2, 5] = -0.0
+        sc[0, nb // 2] = 1.0                               # a fully tied row
+        sc = np.where(np.tril(np.ones((nb, nb), bool))[None], sc, -np.inf).astype(np.float32)
+        budget = so.packed_budget(cu, B, [ks], 0.7, 0, n_sink, n_local)
+        want_c, want_i = so.select_blocks(sc.astype(np.float64), budget, cu, B, n_sink, n_local)
+        shape = sb.Shape(Hq, 1, 128, B, cu, (Hq * 128, 128), (128, 128))
+        kmax = int(budget.max())
+        dev = torch.device("cuda:0")
+        counts = torch.zeros((Hq, nb), dtype=torch.int32, device=dev)
+        idx = torch.zeros((Hq, nb, kmax), dtype=torch.int32, device=dev)
+        sb.stem_select(shape, torch.from_numpy(sc).to(dev), torch.from_numpy(budget).to(dev), n_sink, n_local,
+                       counts, idx, kmax)
+        torch.cuda.synchronize()
+        assert np.array_equal(counts.cpu().numpy(), want_c)
+        assert np.array_equal(idx.cpu().numpy(), want_i[:, :, :kmax])
+
+
+def test_attention_on_given_lists_full_budget_and_random():
+    """Stage 3 alone on caller-made lists: the full causal budget (dense attention) and random
+    ascending lists that hold the diagonal; packed, ragged, GQA 4:1."""
+    w = wl.small("attn_lists", seed=41, num_q_heads=8, num_kv_heads=2, seq_lens=(1300, 640, 77), block_size=128,
+                 k_start=(1, 1, 1), outliers=(1, 1, 1))
+    data = wl.generate(w)
+    qkv = pu.host_arrays(data)
+    cu, B, Hq = w.cu_seqlens, w.block_size, w.num_q_heads
+    R, nbmax = so.total_rows(cu, B)
+    r = np.random.default_rng(42)
+    for mode in ("full", "random"):
+        counts = np.zeros((Hq, R), np.int32)
+        idx = np.full((Hq, R, nbmax), -1, np.int32)
+        for (_, _, nb, row0) in so.sequence_table(cu, B):
+            for i in range(nb):
+                for h in range(Hq):
+                    if mode == "full":
+                        pick = list(range(i + 1))
+                    else:
+                        pick = sorted(set(r.choice(i + 1, size=min(3, i + 1), replace=False).tolist()) | {i})
+                    counts[h, row0 + i] = len(pick)
+                    idx[h, row0 + i, :len(pick)] = pick
+        say("attention lists mode", mode)
+        dev = torch.device("cuda:0")
+        q, k, v = (data[x].to(dev) for x in "qkv")
+        shape = sb.Shape.from_tensors(q, k, B, cu)
+        out = torch.zeros_like(q)
+        lse = torch.zeros((Hq, q.shape[0]), dtype=torch.float32, device=dev)
+        sb.stem_sparse_attn(shape, q, k, v, torch.from_numpy(counts).to(dev), torch.from_numpy(idx).to(dev),
+                            nbmax, w.softmax_scale, out, lse)
+        torch.cuda.synchronize()
+        o_out, o_lse = so.sparse_attention(*qkv, cu, B, counts, idx, w.softmax_scale)
+        pu.check_output(out.float().cpu().numpy(), o_out, mode)
+        assert np.abs(lse.cpu().numpy() - o_lse).max() <= 2e-3
+
+
+def test_outputs_are_deterministic_and_strided_views_work():
+    """Same inputs twice give bit-identical results; Q/K/V given as views of a fused [T, H, d] QKV
+    buffer (non-trivial token stride) give the same result as contiguous tensors."""
+    w = SMALL["packed_b128"]
+    data = wl.generate(w)
+    pf = pu.device_prefill(w, data)
+    a = pf.run().clone()
+    ia = pf.indices.clone()
+    torch.cuda.synchronize()
+    b = pf.run()
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(ia, pf.indices)
+    dev = a.device
+    Hq, Hkv = w.num_q_heads, w.num_kv_heads
+    fused = torch.zeros((w.total_tokens, Hq + 2 * Hkv, 128), dtype=torch.bfloat16, device=dev)
+    fused[:, :Hq] = data["q"].to(dev)
+    fused[:, Hq:Hq + Hkv] = data["k"].to(dev)
+    fused[:, Hq + Hkv:] = data["v"].to(dev)
+    from paper_2603_06274_amd.prefill import StemPrefill
+    pf2 = StemPrefill(fused[:, :Hq], fused[:, Hq:Hq + Hkv], fused[:, Hq + Hkv:], w.cu_seqlens, w.block_size,
+                      w.k_start_blocks, w.mu, w.k_min, w.n_sink, w.n_local, w.beta, w.route_scale,
+                      w.softmax_scale)
+    c = pf2.run()
+    torch.cuda.synchronize()
+    assert torch.equal(pf2.indices, ia) and torch.equal(c, a)

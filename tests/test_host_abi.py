@@ -1,0 +1,109 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every declared symbol,
+does its shape bookkeeping and the Eq. 3 schedule on the host, and rejects bad arguments before
+anything could be launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import stem_oracle as so
+from paper_2603_06274_amd import binding as sb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def make_shape(cu, Hq=4, Hkv=2, d=128, B=64):
+    return sb.Shape(Hq, Hkv, d, B, cu, (Hq * d, d), (Hkv * d, d))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "stem.h")).read()
+    declared = set(re.findall(r"^\s*(?:int|const char\*)\s+(stem_\w+)\s*\(", header, flags=re.M))
+    assert declared == set(sb.EXPORTED)
+    L = ctypes.CDLL(sb.library_path())
+    for name in declared:
+        assert hasattr(L, name), name
+    assert sb.stem_version() >= 100
+    assert sb.stem_strerror(0) == "ok" and "workspace" in sb.stem_strerror(sb.STEM_ERR_WORKSPACE)
+
+
+def test_rows_and_workspace():
+    shape = make_shape([0, 100, 100, 740], B=64)
+    assert sb.stem_rows(shape) == (2 + 0 + 10, 10)
+    assert sb.stem_rows(shape) == so.total_rows([0, 100, 100, 740], 64)
+    q_off, k_off, m_off = sb.stem_workspace_layout(shape)
+    total = sb.stem_workspace_bytes(shape)
+    assert q_off == 0 and k_off >= 4 * 12 * 128 * 4 and m_off >= k_off + 2 * 12 * 128 * 4
+    assert total >= m_off + 2 * 12 * 4 and k_off % 256 == 0 and m_off % 256 == 0
+
+
+@pytest.mark.parametrize("cu,B,ks,mu,k_min,n_sink,n_local", [
+    ([0, 4096], 64, [12], 0.7, 0, 2, 1),
+    ([0, 32768], 128, [25], 0.7, 0, 2, 2),
+    ([0, 131072], 128, [51], 0.7, 0, 2, 2),
+    ([0, 131072], 128, [102.4], 0.7, 54, 4, 4),
+    ([0, 65536], 128, [51.2], 0.7, 54, 4, 4),
+    ([0, 8192, 24576, 57344, 131072], 128, [4, 8, 16, 36], 0.7, 0, 2, 2),
+    ([0, 65536], 128, [512], 1.0, 0, 2, 2),
+    ([0, 65536], 128, [28], 1.0, 0, 2, 2),
+    ([0, 100, 100, 777], 64, [3, 1, 5.5], 0.5, 2, 0, 0),
+    ([0, 6400], 64, [10], 0.7, 0, 1, 3),
+    ([0, 6400], 64, [0], 0.3, 0, 5, 7),
+])
+def test_budget_schedule_matches_oracle(cu, B, ks, mu, k_min, n_sink, n_local):
+    shape = make_shape(cu, B=B)
+    got, kmax = sb.stem_budget_schedule(shape, ks, mu, k_min, n_sink, n_local)
+    want = so.packed_budget(cu, B, ks, mu, k_min, n_sink, n_local)
+    assert got.numpy().tolist() == want.tolist()
+    assert kmax == (int(want.max()) if len(want) else 0)
+
+
+def test_budget_schedule_random_sweep():
+    r = np.random.default_rng(0)
+    for _ in range(200):
+        n = int(r.integers(1, 400))
+        ks = float(r.integers(0, 2 * n)) * (1.0 if r.random() < 0.5 else 0.1)
+        mu = float(r.choice([0.5, 0.6, 0.7, 0.8, 0.9, 1.0]))
+        k_min, n_sink, n_local = int(r.integers(0, 10)), int(r.integers(0, 6)), int(r.integers(0, 6))
+        shape = make_shape([0, n * 64 - int(r.integers(0, 64))], B=64)
+        got, _ = sb.stem_budget_schedule(shape, [ks], mu, k_min, n_sink, n_local)
+        assert got.numpy().tolist() == so.tpd_budget(n, ks, mu, k_min, n_sink, n_local).tolist()
+
+
+def test_bad_arguments_are_rejected_on_the_host():
+    L = sb.lib()
+    good = make_shape([0, 640])
+    n = ctypes.c_size_t()
+    # shape errors
+    assert L.stem_workspace_bytes(make_shape([0, 640], Hq=3, Hkv=2).ref(), ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_workspace_bytes(make_shape([0, 640], d=64).ref(), ctypes.byref(n)) == sb.STEM_ERR_UNSUPPORTED
+    assert L.stem_workspace_bytes(make_shape([0, 640], B=32).ref(), ctypes.byref(n)) == sb.STEM_ERR_UNSUPPORTED
+    assert L.stem_workspace_bytes(make_shape([0, 640, 600]).ref(), ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_workspace_bytes(make_shape([1, 640]).ref(), ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_workspace_bytes(make_shape(list(range(0, 66 * 64, 64))).ref(), ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_workspace_bytes(make_shape([0, 64 * 5000]).ref(), ctypes.byref(n)) == sb.STEM_ERR_UNSUPPORTED
+    bad_stride = sb.Shape(4, 2, 128, 64, [0, 640], (4 * 128 + 4, 128), (2 * 128, 128))
+    assert L.stem_workspace_bytes(bad_stride.ref(), ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_workspace_bytes(None, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
+    # null / misaligned device pointers, short workspace: refused before any launch
+    assert L.stem_pool(good.ref(), None, None, None, None, 0, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_pool(good.ref(), 0x1000, 0x1000, 0x1008, 0x1000, 1 << 30, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_pool(good.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 16, None) == sb.STEM_ERR_WORKSPACE
+    assert L.stem_estimate(good.ref(), 0x1000, 0x1000, 0x1000, 0.2, 1.0, 2, 0x1000, 0x1000, 1 << 30, None) == sb.STEM_ERR_UNSUPPORTED
+    assert L.stem_estimate(good.ref(), 0x1000, 0x1000, 0x1000, 0.2, 1.0, 0, 0x1000, 0x1000, 1 << 30, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_block_scores(good.ref(), 0x1000, 1 << 30, float("nan"), 1.0, 0x1000, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_select(good.ref(), 0x1000, 0x1000, 1, 1, 0x1000, None, 8, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_select(good.ref(), 0x1000, 0x1000, -1, 1, 0x1000, 0x1000, 8, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_select(good.ref(), 0x1000, 0x1000, 3, 3, 0x1000, 0x1000, 4, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_sparse_attn(good.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0, 0.1, 0x1000, None, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_sparse_attn(good.ref(), 0x1000, 0x1000, 0x1000, None, 0x1000, 4, 0.1, 0x1000, None, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_sparse_attn(good.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 4, -1.0, 0x1000, None, None) == sb.STEM_ERR_INVALID_ARG
+    # an empty batch entry list is fine on the host and launches nothing
+    empty = make_shape([0, 0])
+    assert sb.stem_rows(empty) == (0, 0)
+    assert L.stem_pool(empty.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 1 << 20, None) == sb.STEM_OK
+    assert L.stem_sparse_attn(empty.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 4, 0.1, 0x1000, None, None) == sb.STEM_OK
+    with pytest.raises(sb.StemError):
+        sb.stem_rows(make_shape([0, 640], d=64))
