@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the Stem prefill hot path on one MI355X.
+
+One step = stem_estimate -> stem_select -> stem_sparse_attn over one synthetic Llama-3-8B-shaped
+attention layer at 128K tokens (32/8 GQA heads, head_dim 128, block 128, ~8 % block density), all
+inputs resident in HBM.  Prints one JSON line.
+
+  value      dense-equivalent TFLOP/s of the whole path: the FLOPs dense causal attention would
+             spend on the layer (4 d B^2 A Hq) divided by the time of one step
+  roofline   the sparse-attention kernel against the bf16 MFMA peak, from the FLOPs it really
+             executes (4 d B^2 per listed block) and its duration measured with events on the
+             launch stream
+  cpu_baseline  the CPU oracle as it stands, timed on a bounded sample of the same layer and
+             extrapolated by listed-block count (a reported baseline, not a target)
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+# HBM bytes per sparse-attention launch on the 128K layer, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this script (see profiles/); None until measured.
+MEASURED_ATTN_TRAFFIC_BYTES = None
+
+
+def median(xs):
+    xs = sorted(xs)
+    return xs[len(xs) // 2]
+
+
+def cpu_baseline(w, data, dense_flops):
+    """Times the oracle on KV group 0 (stages 1-2 in full, stage 3 on evenly spaced rows) and
+    extrapolates to the layer."""
+    import numpy as np
+    import torch
+    from oracle import stem_oracle as so
+
+    G = w.num_q_heads // w.num_kv_heads
+    q = data["q"][:, :G].float().numpy()
+    k = data["k"][:, :1].float().numpy()
+    v = data["v"][:, :1].float().numpy()
+    t0 = time.perf_counter()
+    q_bar, k_bar, m_v = so.pool_blocks(q, k, v, w.cu_seqlens, w.block_size)
+    scores = so.oam_scores(q_bar, k_bar, m_v, w.cu_seqlens, w.block_size, w.beta, w.route_scale)
+    budget = so.packed_budget(w.cu_seqlens, w.block_size, w.k_start_blocks, w.mu, w.k_min, w.n_sink, w.n_local)
+    counts, indices = so.select_blocks(scores, budget, w.cu_seqlens, w.block_size, w.n_sink, w.n_local)
+    t12 = time.perf_counter() - t0
+    n_rows = 48
+    rows = [int(x) for x in np.linspace(0, w.total_rows - 1, n_rows)]
+    t0 = time.perf_counter()
+    so.sparse_attention(q, k, v, w.cu_seqlens, w.block_size, counts, indices, w.softmax_scale, rows=rows)
+    t3 = time.perf_counter() - t0
+    sampled_blocks = int(counts[:, rows].sum())
+    group_blocks = int(counts.sum())
+    t_layer = w.num_kv_heads * (t12 + t3 * group_blocks / max(sampled_blocks, 1))
+    return {
+        "value": round(dense_flops / t_layer / 1e12, 4), "unit": "TFLOP/s (dense-equivalent)",
+        "cores": torch.get_num_threads(), "kind": "oracle",
+        "sample": "KV group 0 (%d of %d query heads): stages 1-2 in full (%.1f s), stage 3 on %d of %d "
+                  "query-block rows (%.1f s, %d listed blocks); layer time extrapolated by listed-block "
+                  "count to %.0f s" % (G, w.num_q_heads, t12, n_rows, w.total_rows, t3, sampled_blocks, t_layer),
+        "extrapolated_layer_seconds": round(t_layer, 1),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama8b_128k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is a one-GPU hot path (no collectives, no sharding); run with --gpus 1")
+
+    import torch
+    from paper_2603_06274_amd import binding, workloads
+    from paper_2603_06274_amd.prefill import StemPrefill
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    binding.lib()
+    w = workloads.BENCHMARK_CONFIGS[args.workload]
+    data = workloads.generate(w)
+    dev = torch.device("cuda:0")
+    pf = StemPrefill(*(data[x].to(dev) for x in "qkv"), w.cu_seqlens, w.block_size, w.k_start_blocks, w.mu,
+                     w.k_min, w.n_sink, w.n_local, w.beta, w.route_scale, w.softmax_scale)
+
+    d, B, Hq, Hkv, T, R = w.head_dim, w.block_size, w.num_q_heads, w.num_kv_heads, w.total_tokens, w.total_rows
+    dense_flops = 4.0 * d * B * B * w.admissible_blocks * Hq
+
+    for _ in range(args.warmup):
+        pf.run()
+    torch.cuda.synchronize()
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        ev[s][0].record()
+        pf.estimate()
+        ev[s][1].record()
+        pf.select()
+        ev[s][2].record()
+        pf.attend()
+        ev[s][3].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    t_est = median([e[0].elapsed_time(e[1]) for e in ev])
+    t_sel = median([e[1].elapsed_time(e[2]) for e in ev])
+    attn_ms = [e[2].elapsed_time(e[3]) for e in ev]
+    t_attn_avg = sum(attn_ms) / len(attn_ms)
+
+    listed = int(pf.counts.sum().item())
+    density = listed / (w.admissible_blocks * Hq)
+    attn_flops = 4.0 * d * B * B * listed
+    attn_tflops = attn_flops / (t_attn_avg * 1e-3) / 1e12
+
+    # the two kernels of stage 1, timed on their own (outside the timed region above)
+    def time_call(fn, n=10):
+        fn()
+        torch.cuda.synchronize()
+        out = []
+        for _ in range(n):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            b.synchronize()
+            out.append(a.elapsed_time(b))
+        return sum(out) / len(out)
+
+    t_pool = time_call(pf.pool)
+    t_scores = time_call(pf.block_scores)
+    pool_bytes = 2.0 * d * T * (Hq + 2 * Hkv) + 4.0 * d * R * (Hq + Hkv) + 4.0 * R * Hkv
+    pool_gbs = pool_bytes / (t_pool * 1e-3) / 1e9
+
+    value = dense_flops / (ms_per_step * 1e-3) / 1e12
+    result = {
+        "metric": "sparse prefill attention, dense-equivalent TFLOP/s at 128K (estimate + select + attention, one layer)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "tokens": T, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d, "block": B,
+                   "k_start_blocks": list(w.k_start_blocks), "mu": w.mu, "beta": w.beta,
+                   "n_sink": w.n_sink, "n_local": w.n_local, "density": round(density, 5),
+                   "listed_blocks": listed},
+        "stages_ms": {"estimate": round(t_est, 4), "select": round(t_sel, 4), "attention": round(t_attn_avg, 4),
+                      "pool_kernel": round(t_pool, 4), "scores_kernel": round(t_scores, 4)},
+        "attention_dense_equiv_tflops": round(dense_flops / (t_attn_avg * 1e-3) / 1e12, 2),
+        "roofline": {"kernel": "sparse_attn_kernel", "bound": "mfma", "achieved": round(attn_tflops, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": MEASURED_ATTN_TRAFFIC_BYTES},
+        "estimate_roofline": {"kernel": "pool_kernel", "bound": "hbm", "achieved": round(pool_gbs, 1),
+                              "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(pool_gbs / PEAK_HBM_GBS, 4),
+                              "algorithmic_bytes": pool_bytes},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, data, dense_flops)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

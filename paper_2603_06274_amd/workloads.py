@@ -185,4 +185,4 @@ def generate(w: Workload) -> Dict[str, torch.Tensor]:
 
 def with_budget(w: Workload, k_start: Sequence[int], mu: float, name_suffix: str) -> Workload:
     """Same tensors (same seed and shape), different budget schedule."""
-    return replace(w, k_start_blocks=tuple(k_start), mu=mu, name=w.name + name_suffix)
+    return replace(w, k_start_blocks=tuple(k_start), mu=mu, name=w.name + name_suffix, target_density=0.0)
