@@ -1,16 +1,27 @@
 // Stage 3 (Algorithm 1 step 3d): block-sparse causal flash attention over the selected key blocks.
 //
-// One workgroup owns one (query head, query block): B query rows, 32 per wavefront.  For every
-// listed key block the workgroup stages K (row-major, 16-byte chunks XOR-swizzled by row) and V
-// (transposed to [d][key]) in LDS, and each wave runs
+// One workgroup owns one (query head, query block): B query rows, 32 per wavefront.  Per listed key
+// block each wave runs
 //     S^T = K Q^T      v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = the wave's Q rows (regs)
-//     online softmax   in the exp2 domain, fp32, one query column per lane
-//     O^T += V^T P^T   A = V^T rows from LDS, B = P^T taken straight from the S^T accumulators
+//     online softmax   exp2 domain, fp32, one query column per lane
+//     O^T += V^T P^T   A = V^T rows read from row-major V in LDS with ds_read_b64_tr_b16,
+//                      B = P^T taken straight from the S^T accumulators
 // Computing the transposed products puts one query in one lane, so the softmax row reductions are
 // in-lane plus a single exchange with lane^32, and the S^T accumulator registers are already in
 // the B-operand layout of the second product: the key rows of each 32-row S^T tile are fed in an
 // order (bits 2 and 3 of the row index swapped) that makes each lane's eight accumulator values of
 // a 16-key step eight consecutive keys.
+//
+// K and V blocks go from global memory straight into LDS (global_load_lds_dwordx4, no staging
+// registers), one buffer each, refilled in split phases: the next K block is requested as soon as
+// every wave has finished S^T and lands while softmax and O^T run; the V block is requested at
+// the top of the iteration and lands while S^T and softmax run.  Two workgroups share a CU, so one
+// workgroup's matrix work overlaps the other's softmax and waits.
+//
+// LDS layouts (256-byte rows): K has its 16-byte chunks XORed with (row & 15), so the 32 rows a
+// b128 operand read touches spread over all banks; V has its 64-byte groups XORed with (row & 3),
+// which does the same for the 4-row x 64-byte footprint of a transposing read.  The swizzle is
+// applied on the global side (each lane fetches the chunk that belongs at its LDS position).
 #include "stem_common.h"
 
 namespace stem {
@@ -19,6 +30,9 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 x) { return __builtin_bit_cast(bf16x8_t, x); }
 
@@ -31,27 +45,51 @@ __device__ __forceinline__ int swap_bits_2_3(int x) {
     return (x & ~12) | ((x & 4) << 1) | ((x & 8) >> 1);
 }
 
-template <int B>
-struct AttnSmem {
-    static constexpr int kKRow = kHeadDim * 2;         // bytes per K row
-    static constexpr int kVtRow = B * 2 + 16;          // bytes per V^T row (padded)
-    static constexpr int kKBytes = B * kKRow;
-    static constexpr int kVtBytes = kHeadDim * kVtRow;
-};
+// Workgroup barrier without the memory fence of __syncthreads (which would wait for every
+// outstanding global->LDS load); the waits are placed by hand.
+#define STEM_BARRIER()                              \
+    do {                                            \
+        asm volatile("" ::: "memory");              \
+        __builtin_amdgcn_s_barrier();               \
+        asm volatile("" ::: "memory");              \
+    } while (0)
+// s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt[3:0], expcnt[6:4]=7, lgkmcnt[11:8]=15); the
+// builtin, unlike inline asm, is seen by the compiler's own wait-count bookkeeping.
+#define STEM_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | (N))
 
+constexpr int kRowBytes = kHeadDim * 2;               // one K or V row in LDS
+
+// Requests one B x 128 bf16 block (rows tok0 .. tok0+B-1 of one KV head) into LDS.  Every wave
+// issues 8 loads of 1 KiB (4 rows); rows past the end of the sequence re-read its last token, so
+// LDS never holds uninitialised bits (their keys are masked, their values get weight 0).
+template <int B, bool kIsV>
+__device__ __forceinline__ void request_block(const uint16_t* __restrict__ head, int64_t stride,
+                                              int tok0, int seq_hi, unsigned char* __restrict__ lds,
+                                              int w, int lane) {
+    constexpr int NW = B / 32;
+    const int sub = lane >> 4, pc = lane & 15;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int cidx = u * NW + w;                   // 1 KiB slice of the block
+        const int row = cidx * 4 + sub;
+        const int c = kIsV ? (pc ^ ((row & 3) << 2)) : (pc ^ (row & 15));
+        const int tok = min(tok0 + row, seq_hi - 1);
+        const uint16_t* src = head + (int64_t)tok * stride + c * 8;
+        __builtin_amdgcn_global_load_lds(src, (lds_void_t*)(lds + cidx * 1024), 16, 0, 0);
+    }
+}
+
+// The body takes the two LDS buffers as __restrict__ parameters: once inlined, every access carries
+// alias-scope information, which lets the compiler's wait-count insertion tell a read of one buffer
+// from an in-flight global->LDS load into the other (otherwise it waits for all of them).
 template <int B>
-__global__ __launch_bounds__(B * 2) void sparse_attn_kernel(
+__device__ __forceinline__ void sparse_attn_body(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ counts, const int32_t* __restrict__ indices,
-    uint16_t* __restrict__ out, float* __restrict__ lse, SeqTable seq, int Hq, int R, int G, int T,
-    int kmax, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh, float scale,
-    int items_per_xcd) {
-    constexpr int NT = B * 2;                          // threads
+    uint16_t* __restrict__ out, float* __restrict__ lse, const SeqTable& seq, int Hq, int R, int G,
+    int T, int kmax, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh, float scale,
+    int items_per_xcd, unsigned char* __restrict__ k_lds, unsigned char* __restrict__ v_lds) {
     constexpr int KT = B / 32;                         // 32-key tiles per block
-    using S = AttnSmem<B>;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char* k_lds = smem;
-    unsigned char* vt_lds = smem + S::kKBytes;
 
     // ---- which (head, row): consecutive workgroup ids go to different XCDs, so give every XCD a
     // contiguous range of the (kv head, row descending, head in group) order ----
@@ -68,11 +106,22 @@ __global__ __launch_bounds__(B * 2) void sparse_attn_kernel(
     const int seq_lo = seq.tok_start[s], seq_hi = seq.tok_start[s + 1];
     const int tok_q0 = seq_lo + i * B;
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hi = lane >> 5;
     const int qrow = w * 32 + col;                     // query row inside the block
     const int tok_q = tok_q0 + qrow;
     const bool q_valid = tok_q < seq_hi;
+
+    const int cnt = min(counts[(int64_t)h * R + r], kmax);
+    const int32_t* list = indices + ((int64_t)h * R + r) * kmax;
+    const uint16_t* k_head = k + (int64_t)g * kv_sh;
+    const uint16_t* v_head = v + (int64_t)g * kv_sh;
+
+    // first usable list entry (entries outside 0..i are skipped)
+    int it = 0;
+    while (it < cnt && (list[it] < 0 || list[it] > i)) ++it;
+    if (it < cnt) request_block<B, false>(k_head, kv_st, seq_lo + list[it] * B, seq_hi, k_lds, w, lane);
 
     // ---- Q rows of this wave as B operands: 8 k-steps of 16 along d ----
     bf16x8_t q_reg[8];
@@ -91,63 +140,31 @@ __global__ __launch_bounds__(B * 2) void sparse_attn_kernel(
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int x = 0; x < 16; ++x) o_acc[dt][x] = 0.f;
-    float m_run = -__builtin_huge_valf();              // running max of raw scores
+    const float neg_inf = -__builtin_huge_valf();
+    float m_ref = neg_inf;                             // softmax reference (raw score units)
     float l_run = 0.f;                                 // this lane's share of the softmax sum
     const float sl2 = scale * 1.4426950408889634f;
 
-    const int cnt = min(counts[(int64_t)h * R + r], kmax);
-    const int32_t* list = indices + ((int64_t)h * R + r) * kmax;
-    const uint16_t* k_head = k + (int64_t)g * kv_sh;
-    const uint16_t* v_head = v + (int64_t)g * kv_sh;
+    // per-lane LDS offsets that do not change between blocks
+    const int k_row = swap_bits_2_3(col);              // + t*32 ; (row & 15) == (k_row & 15)
+    const int k_base = k_row * kRowBytes;
+    const int k_swz = k_row & 15;
+    // transposing V read: lane l fetches row key0 + 8*hi + (l%16)/4 (+4), 8 bytes at column
+    // dt*32 + 16*((l>>4)&1) + 4*(l&3); the 64-byte group index dt is XORed with (row & 3)
+    const int v_row = hi * 8 + ((lane & 15) >> 2);
+    const int v_in = (((lane >> 4) & 1) << 5) + ((lane & 3) << 3);
+    const int v_swz = v_row & 3;                       // key0 and the +4 keep (row & 3)
 
-    for (int it = 0; it < cnt; ++it) {
+    while (it < cnt) {
         const int j = list[it];
-        if (j < 0 || j > i) continue;                  // uniform over the workgroup
-        const int tok_k0 = seq_lo + j * B;
+        int it_next = it + 1;
+        while (it_next < cnt && (list[it_next] < 0 || list[it_next] > i)) ++it_next;
+        const bool has_next = it_next < cnt;
         const bool diag = (j == i);
 
-        __syncthreads();                               // everyone is done with the previous block
-        // ---- stage K: B rows x 16 chunks of 16 B, chunk position XORed with (row & 15) ----
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int idx = tid + NT * u;
-            const int row = idx >> 4, c = idx & 15;
-            uint4 x = make_uint4(0u, 0u, 0u, 0u);
-            if (tok_k0 + row < seq_hi)
-                x = *reinterpret_cast<const uint4*>(k_head + (int64_t)(tok_k0 + row) * kv_st + c * 8);
-            *reinterpret_cast<uint4*>(k_lds + row * S::kKRow + ((c ^ (row & 15)) << 4)) = x;
-        }
-        // ---- stage V transposed: a unit is 4 keys x 8 columns -> eight 8-byte writes ----
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int idx = tid + NT * u;
-            const int m_lo = idx & 15, c_lo = (idx >> 4) & 3, rest = idx >> 6;
-            const int c = (rest & 3) * 4 + c_lo, m = (rest >> 2) * 16 + m_lo;
-            uint4 x[4];
-#pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                const int row = 4 * m + qd;
-                x[qd] = make_uint4(0u, 0u, 0u, 0u);
-                if (tok_k0 + row < seq_hi)
-                    x[qd] = *reinterpret_cast<const uint4*>(v_head + (int64_t)(tok_k0 + row) * kv_st + c * 8);
-            }
-            const uint32_t w0[4] = {x[0].x, x[0].y, x[0].z, x[0].w};
-            const uint32_t w1[4] = {x[1].x, x[1].y, x[1].z, x[1].w};
-            const uint32_t w2[4] = {x[2].x, x[2].y, x[2].z, x[2].w};
-            const uint32_t w3[4] = {x[3].x, x[3].y, x[3].z, x[3].w};
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                uint2 even, odd;                       // columns 2*e2 and 2*e2+1, keys 4m..4m+3
-                even.x = (w0[e2] & 0xffffu) | (w1[e2] << 16);
-                even.y = (w2[e2] & 0xffffu) | (w3[e2] << 16);
-                odd.x = (w0[e2] >> 16) | (w1[e2] & 0xffff0000u);
-                odd.y = (w2[e2] >> 16) | (w3[e2] & 0xffff0000u);
-                const int d0 = c * 8 + 2 * e2;
-                *reinterpret_cast<uint2*>(vt_lds + d0 * S::kVtRow + m * 8) = even;
-                *reinterpret_cast<uint2*>(vt_lds + (d0 + 1) * S::kVtRow + m * 8) = odd;
-            }
-        }
-        __syncthreads();
+        STEM_WAIT_VMCNT(0);
+        STEM_BARRIER();                                // K(j) is in LDS; V buffer is free
+        request_block<B, true>(v_head, kv_st, seq_lo + j * B, seq_hi, v_lds, w, lane);
 
         // ---- S^T = K Q^T : KT tiles of 32 keys x 32 queries ----
         f32x16_t s_acc[KT];
@@ -155,15 +172,17 @@ __global__ __launch_bounds__(B * 2) void sparse_attn_kernel(
         for (int t = 0; t < KT; ++t) {
 #pragma unroll
             for (int x = 0; x < 16; ++x) s_acc[t][x] = 0.f;
-            const int row = t * 32 + swap_bits_2_3(col);
-            const unsigned char* base = k_lds + row * S::kKRow;
+            const unsigned char* base = k_lds + t * 32 * kRowBytes + k_base;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
                 const int c = ks * 2 + hi;
-                const uint4 a = *reinterpret_cast<const uint4*>(base + ((c ^ (row & 15)) << 4));
+                const uint4 a = *reinterpret_cast<const uint4*>(base + ((c ^ k_swz) << 4));
                 s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), q_reg[ks], s_acc[t], 0, 0, 0);
             }
         }
+        STEM_BARRIER();                                // every wave is done with K(j)
+        if (has_next)
+            request_block<B, false>(k_head, kv_st, seq_lo + list[it_next] * B, seq_hi, k_lds, w, lane);
 
         // ---- causal mask inside the diagonal block: accumulator x of tile t is key
         //      t*32 + 16*(x/8) + 8*hi + x%8 of the block ----
@@ -173,21 +192,30 @@ __global__ __launch_bounds__(B * 2) void sparse_attn_kernel(
 #pragma unroll
                 for (int x = 0; x < 16; ++x) {
                     const int key = t * 32 + 16 * (x >> 3) + 8 * hi + (x & 7);
-                    if (key > qrow) s_acc[t][x] = -__builtin_huge_valf();
+                    if (key > qrow) s_acc[t][x] = neg_inf;
                 }
         }
 
-        // ---- online softmax ----
+        // ---- online softmax; the reference only moves when the block maximum exceeds it by
+        //      more than 2^8 in the exp2 domain, so rescaling O is rare ----
         float mx = s_acc[0][0];
 #pragma unroll
         for (int t = 0; t < KT; ++t)
 #pragma unroll
             for (int x = 0; x < 16; ++x) mx = fmaxf(mx, s_acc[t][x]);
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = (m_new == -__builtin_huge_valf()) ? 0.f : m_new;
-        const float corr = __builtin_amdgcn_exp2f((m_run - m_use) * sl2);
-        const float off = m_use * sl2;
+        const bool move = (mx - m_ref) * sl2 > 8.0f || m_ref == neg_inf;
+        if (__builtin_amdgcn_ballot_w64(move && mx > neg_inf) != 0) {
+            const float m_new = (move && mx > neg_inf) ? mx : m_ref;
+            const float corr = (m_ref == neg_inf) ? 0.f : __builtin_amdgcn_exp2f((m_ref - m_new) * sl2);
+            m_ref = m_new;
+            l_run *= corr;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int x = 0; x < 16; ++x) o_acc[dt][x] *= corr;
+        }
+        const float off = (m_ref == neg_inf) ? 0.f : m_ref * sl2;
         float psum = 0.f;
         uint32_t p_pk[KT][8];                          // bf16 pairs: [tile][16-key step * 4 + pair]
 #pragma unroll
@@ -199,12 +227,10 @@ __global__ __launch_bounds__(B * 2) void sparse_attn_kernel(
                 psum += p0 + p1;
                 p_pk[t][x >> 1] = pack_bf16(p0, p1);
             }
-        l_run = l_run * corr + psum;
-        m_run = m_new;
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) o_acc[dt][x] *= corr;
+        l_run += psum;
+
+        if (has_next) STEM_WAIT_VMCNT(8); else STEM_WAIT_VMCNT(0);
+        STEM_BARRIER();                                // V(j) is in LDS
 
         // ---- O^T += V^T P^T ----
 #pragma unroll
@@ -213,13 +239,18 @@ __global__ __launch_bounds__(B * 2) void sparse_attn_kernel(
             for (int u = 0; u < 2; ++u) {
                 const uint4 pb = make_uint4(p_pk[t][u * 4], p_pk[t][u * 4 + 1], p_pk[t][u * 4 + 2],
                                             p_pk[t][u * 4 + 3]);
-                const int key0 = t * 32 + 16 * u + 8 * hi;
+                const unsigned char* rowp = v_lds + (t * 32 + 16 * u + v_row) * kRowBytes + v_in;
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt) {
-                    const uint4 a = *reinterpret_cast<const uint4*>(vt_lds + (dt * 32 + col) * S::kVtRow + key0 * 2);
+                    const unsigned char* p0 = rowp + ((dt ^ v_swz) << 6);
+                    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)p0);
+                    const s16x4_t hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p0 + 4 * kRowBytes));
+                    const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi4);
+                    const uint4 a = make_uint4(lo2.x, lo2.y, hi2.x, hi2.y);
                     o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(pb), o_acc[dt], 0, 0, 0);
                 }
             }
+        it = it_next;
     }
 
     // ---- normalise and store: accumulator x of d tile dt is column dt*32 + 8*(x/4) + 4*hi + x%4 ----
@@ -237,8 +268,21 @@ __global__ __launch_bounds__(B * 2) void sparse_attn_kernel(
                 *reinterpret_cast<uint2*>(dst + dt * 32 + x4 * 8) = pk;
             }
         if (lse != nullptr && hi == 0)
-            lse[(int64_t)h * T + tok_q] = l_tot > 0.f ? m_run * scale + __logf(l_tot) : -__builtin_huge_valf();
+            lse[(int64_t)h * T + tok_q] = l_tot > 0.f ? m_ref * scale + __logf(l_tot) : neg_inf;
     }
+}
+
+template <int B>
+__global__ __launch_bounds__(B * 2, 2) void sparse_attn_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int32_t* __restrict__ counts, const int32_t* __restrict__ indices,
+    uint16_t* __restrict__ out, float* __restrict__ lse, SeqTable seq, int Hq, int R, int G, int T,
+    int kmax, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh, float scale,
+    int items_per_xcd) {
+    __shared__ __attribute__((aligned(1024))) unsigned char k_lds[B * kRowBytes];
+    __shared__ __attribute__((aligned(1024))) unsigned char v_lds[B * kRowBytes];
+    sparse_attn_body<B>(q, k, v, counts, indices, out, lse, seq, Hq, R, G, T, kmax, q_st, q_sh, kv_st,
+                        kv_sh, scale, items_per_xcd, k_lds, v_lds);
 }
 
 int launch_sparse_attn(const Problem& p, const void* q, const void* k, const void* v,
@@ -252,23 +296,14 @@ int launch_sparse_attn(const Problem& p, const void* q, const void* k, const voi
     const uint16_t* kk = static_cast<const uint16_t*>(k);
     const uint16_t* vv = static_cast<const uint16_t*>(v);
     uint16_t* oo = static_cast<uint16_t*>(out);
-#define STEM_ATTN_LAUNCH(BS)                                                                        \
-    do {                                                                                            \
-        constexpr int smem = AttnSmem<BS>::kKBytes + AttnSmem<BS>::kVtBytes;                        \
-        static bool configured = false;                                                             \
-        if (!configured) {                                                                          \
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(sparse_attn_kernel<BS>),          \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess) \
-                return STEM_ERR_HIP;                                                                \
-            configured = true;                                                                      \
-        }                                                                                           \
-        hipLaunchKernelGGL(sparse_attn_kernel<BS>, grid, dim3(BS * 2), smem, stream, qq, kk, vv,    \
-                           counts, indices, oo, lse, p.seq, p.Hq, p.R, p.G, p.T, kmax, p.q_st,      \
-                           p.q_sh, p.kv_st, p.kv_sh, softmax_scale, (int)per_xcd);                  \
-    } while (0)
-    if (p.B == 128) STEM_ATTN_LAUNCH(128);
-    else STEM_ATTN_LAUNCH(64);
-#undef STEM_ATTN_LAUNCH
+    if (p.B == 128)
+        hipLaunchKernelGGL(sparse_attn_kernel<128>, grid, dim3(256), 0, stream, qq, kk, vv, counts,
+                           indices, oo, lse, p.seq, p.Hq, p.R, p.G, p.T, kmax, p.q_st, p.q_sh,
+                           p.kv_st, p.kv_sh, softmax_scale, (int)per_xcd);
+    else
+        hipLaunchKernelGGL(sparse_attn_kernel<64>, grid, dim3(128), 0, stream, qq, kk, vv, counts,
+                           indices, oo, lse, p.seq, p.Hq, p.R, p.G, p.T, kmax, p.q_st, p.q_sh,
+                           p.kv_st, p.kv_sh, softmax_scale, (int)per_xcd);
     return check_launch();
 }
 
