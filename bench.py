@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama8b_128k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy, the known-size dispatch the rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is a one-GPU hot path (no collectives, no sharding); run with --gpus 1")
@@ -97,6 +100,13 @@ def main():
 
     d, B, Hq, Hkv, T, R = w.head_dim, w.block_size, w.num_q_heads, w.num_kv_heads, w.total_tokens, w.total_rows
     dense_flops = 4.0 * d * B * B * w.admissible_blocks * Hq
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         pf.run()

@@ -12,7 +12,9 @@ from typing import Optional, Sequence, Tuple
 
 import torch
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libstem_hip.so")
+# STEM_HIP_LIBRARY overrides the in-tree build (to try another build of the same ABI).
+_LIB_PATH = os.environ.get("STEM_HIP_LIBRARY") or os.path.join(
+    os.path.dirname(os.path.abspath(__file__)), "libstem_hip.so")
 _lib = None
 
 STEM_OK = 0

@@ -57,26 +57,51 @@ __device__ __forceinline__ int swap_bits_2_3(int x) {
 // builtin, unlike inline asm, is seen by the compiler's own wait-count bookkeeping.
 #define STEM_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | (N))
 
+// Nothing is scheduled across this point: keeps the next group of LDS operand reads ahead of the
+// matrix instructions that consume the current group.
+#define STEM_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
 constexpr int kRowBytes = kHeadDim * 2;               // one K or V row in LDS
 
-// Requests one B x 128 bf16 block (rows tok0 .. tok0+B-1 of one KV head) into LDS.  Every wave
-// issues 8 loads of 1 KiB (4 rows); rows past the end of the sequence re-read its last token, so
-// LDS never holds uninitialised bits (their keys are masked, their values get weight 0).
-template <int B, bool kIsV>
-__device__ __forceinline__ void request_block(const uint16_t* __restrict__ head, int64_t stride,
-                                              int tok0, int seq_hi, unsigned char* __restrict__ lds,
-                                              int w, int lane) {
-    constexpr int NW = B / 32;
-    const int sub = lane >> 4, pc = lane & 15;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        const int cidx = u * NW + w;                   // 1 KiB slice of the block
-        const int row = cidx * 4 + sub;
-        const int c = kIsV ? (pc ^ ((row & 3) << 2)) : (pc ^ (row & 15));
-        const int tok = min(tok0 + row, seq_hi - 1);
-        const uint16_t* src = head + (int64_t)tok * stride + c * 8;
-        __builtin_amdgcn_global_load_lds(src, (lds_void_t*)(lds + cidx * 1024), 16, 0, 0);
+// One 1 KiB slice (4 rows) of a B x 128 bf16 block, global -> LDS.  A block is 8 slices per wave:
+// wave w issues slices u*NW + w, u = 0..7, so that the row's swizzle term does not depend on u (for
+// B = 64 it depends on the parity of u only).  Requests are issued one or two at a time between
+// groups of matrix instructions, never as a burst: the texture-address unit takes a wave's 1 KiB
+// request at 64 B/clk, and a wave that finds its queue full cannot issue anything else.
+//
+// The loads use buffer addressing: a per-block resource whose base is the block's first row in
+// this KV head and whose size ends with the sequence's last row, so rows past the end of a
+// partial last block (and past the end of the tensor) are never read and arrive in LDS as zeros
+// (their keys are masked by causality, their values get weight 0).  The per-lane byte offset is
+// computed once per kernel; a slice costs one vector add.
+struct BlockRequest {
+    __amdgpu_buffer_rsrc_t rsrc;
+    uint32_t lane_off[2];           // per-lane byte offset for even / odd u
+    uint32_t slice_step;            // bytes between the rows of slices u and u+1 of one wave
+
+    __device__ __forceinline__ void issue(int u, unsigned char* __restrict__ slice0) const {
+        // slice0 = LDS address of this wave's slice for u = 0; slice u lies u*NW KiB further on
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_t*)(slice0 + u * (int)(slice_lds_step)), 16,
+                                                 lane_off[u & 1] + u * slice_step, 0, 0, 0);
     }
+    int slice_lds_step;
+};
+
+__device__ __forceinline__ BlockRequest make_request(const unsigned char* block_base, int rows_left,
+                                                     int64_t row_bytes, uint32_t off_even, uint32_t off_odd,
+                                                     int waves) {
+    BlockRequest rq;
+    // bytes from the block's first row to the end of the last existing row of this head
+    int64_t limit = (int64_t)(rows_left - 1) * row_bytes + kHeadDim * 2;
+    if (limit > 0xffffffffll) limit = 0xffffffffll;
+    // raw buffer (stride 0): num_records in bytes, loads beyond it return zero; 0x00020000 is the
+    // gfx9-family descriptor word for untyped 32-bit data
+    rq.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(block_base), 0, (int)(uint32_t)limit, 0x00020000);
+    rq.lane_off[0] = off_even;
+    rq.lane_off[1] = off_odd;
+    rq.slice_step = (uint32_t)(waves * 4 * row_bytes);
+    rq.slice_lds_step = waves * 1024;
+    return rq;
 }
 
 // The body takes the two LDS buffers as __restrict__ parameters: once inlined, every access carries
@@ -90,6 +115,9 @@ __device__ __forceinline__ void sparse_attn_body(
     int T, int kmax, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh, float scale,
     int items_per_xcd, unsigned char* __restrict__ k_lds, unsigned char* __restrict__ v_lds) {
     constexpr int KT = B / 32;                         // 32-key tiles per block
+    // the 8 slice requests of a block go out over the first kRequestGroups groups of 4 matrix
+    // instructions of a phase (a phase has KT*2 groups)
+    constexpr int kRequestGroups = (KT * 2 >= 8) ? 4 : KT * 2;
 
     // ---- which (head, row): consecutive workgroup ids go to different XCDs, so give every XCD a
     // contiguous range of the (kv head, row descending, head in group) order ----
@@ -118,10 +146,34 @@ __device__ __forceinline__ void sparse_attn_body(
     const uint16_t* k_head = k + (int64_t)g * kv_sh;
     const uint16_t* v_head = v + (int64_t)g * kv_sh;
 
+    // per-lane byte offsets of the block requests (see request_block)
+    const int64_t row_bytes = kv_st * 2;
+    const int lrow = w * 4 + (lane >> 4), pc = lane & 15;
+    const uint32_t lane_row_off = (uint32_t)(lrow * row_bytes);
+    const uint32_t k_off_even = lane_row_off + ((pc ^ (lrow & 15)) << 4);
+    const uint32_t k_off_odd = (B == 128) ? k_off_even : lane_row_off + ((pc ^ ((lrow + 8) & 15)) << 4);
+    const uint32_t v_off = lane_row_off + ((pc ^ ((lrow & 3) << 2)) << 4);
+    auto k_request = [&](int j) {
+        const int tok0 = seq_lo + j * B;
+        return make_request(reinterpret_cast<const unsigned char*>(k_head + (int64_t)tok0 * kv_st), seq_hi - tok0,
+                            row_bytes, k_off_even, k_off_odd, B / 32);
+    };
+    auto v_request = [&](int j) {
+        const int tok0 = seq_lo + j * B;
+        return make_request(reinterpret_cast<const unsigned char*>(v_head + (int64_t)tok0 * kv_st), seq_hi - tok0,
+                            row_bytes, v_off, v_off, B / 32);
+    };
+    unsigned char* k_slice0 = k_lds + w * 1024;        // this wave's first request slice
+    unsigned char* v_slice0 = v_lds + w * 1024;
+
     // first usable list entry (entries outside 0..i are skipped)
     int it = 0;
     while (it < cnt && (list[it] < 0 || list[it] > i)) ++it;
-    if (it < cnt) request_block<B, false>(k_head, kv_st, seq_lo + list[it] * B, seq_hi, k_lds, w, lane);
+    if (it < cnt) {
+        const auto rq = k_request(list[it]);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) rq.issue(u, k_slice0);
+    }
 
     // ---- Q rows of this wave as B operands: 8 k-steps of 16 along d ----
     bf16x8_t q_reg[8];
@@ -145,16 +197,37 @@ __device__ __forceinline__ void sparse_attn_body(
     float l_run = 0.f;                                 // this lane's share of the softmax sum
     const float sl2 = scale * 1.4426950408889634f;
 
-    // per-lane LDS offsets that do not change between blocks
+    // per-lane LDS addresses that do not change between blocks
     const int k_row = swap_bits_2_3(col);              // + t*32 ; (row & 15) == (k_row & 15)
-    const int k_base = k_row * kRowBytes;
+    const unsigned char* k_rd = k_lds + k_row * kRowBytes;
     const int k_swz = k_row & 15;
     // transposing V read: lane l fetches row key0 + 8*hi + (l%16)/4 (+4), 8 bytes at column
     // dt*32 + 16*((l>>4)&1) + 4*(l&3); the 64-byte group index dt is XORed with (row & 3)
     const int v_row = hi * 8 + ((lane & 15) >> 2);
-    const int v_in = (((lane >> 4) & 1) << 5) + ((lane & 3) << 3);
     const int v_swz = v_row & 3;                       // key0 and the +4 keep (row & 3)
+    const unsigned char* v_rd = v_lds + v_row * kRowBytes + (((lane >> 4) & 1) << 5) + ((lane & 3) << 3);
 
+    // operand fetches, written so that the next group of LDS reads is issued before the matrix
+    // instructions of the current group
+    auto load_k_half = [&](int t, int half, uint4* dst) {
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const int c = (half * 4 + x) * 2 + hi;
+            dst[x] = *reinterpret_cast<const uint4*>(k_rd + t * 32 * kRowBytes + ((c ^ k_swz) << 4));
+        }
+    };
+    auto load_v_step = [&](int step, uint4* dst) {     // step = 16 keys; 4 d tiles x 8 keys
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            const unsigned char* p0 = v_rd + step * 16 * kRowBytes + ((dt ^ v_swz) << 6);
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)p0);
+            const s16x4_t up = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p0 + 4 * kRowBytes));
+            const uint2 lo2 = __builtin_bit_cast(uint2, lo), up2 = __builtin_bit_cast(uint2, up);
+            dst[dt] = make_uint4(lo2.x, lo2.y, up2.x, up2.y);
+        }
+    };
+
+    bool first_block = true;
     while (it < cnt) {
         const int j = list[it];
         int it_next = it + 1;
@@ -164,97 +237,141 @@ __device__ __forceinline__ void sparse_attn_body(
 
         STEM_WAIT_VMCNT(0);
         STEM_BARRIER();                                // K(j) is in LDS; V buffer is free
-        request_block<B, true>(v_head, kv_st, seq_lo + j * B, seq_hi, v_lds, w, lane);
+        const auto v_rq = v_request(j);                // issued two slices at a time inside S^T
 
         // ---- S^T = K Q^T : KT tiles of 32 keys x 32 queries ----
         f32x16_t s_acc[KT];
+        {
+            uint4 ka[2][4];
+            load_k_half(0, 0, ka[0]);
+            STEM_SCHED_FENCE();
 #pragma unroll
-        for (int t = 0; t < KT; ++t) {
+            for (int st = 0; st < KT * 2; ++st) {
+                const int t = st >> 1, half = st & 1;
+                if (st + 1 < KT * 2) load_k_half((st + 1) >> 1, (st + 1) & 1, ka[(st + 1) & 1]);
+                if (st < kRequestGroups) {
 #pragma unroll
-            for (int x = 0; x < 16; ++x) s_acc[t][x] = 0.f;
-            const unsigned char* base = k_lds + t * 32 * kRowBytes + k_base;
+                    for (int x = 0; x < 8 / kRequestGroups; ++x) v_rq.issue(st * (8 / kRequestGroups) + x, v_slice0);
+                }
+                STEM_SCHED_FENCE();
+                if (half == 0) {
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const int c = ks * 2 + hi;
-                const uint4 a = *reinterpret_cast<const uint4*>(base + ((c ^ k_swz) << 4));
-                s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), q_reg[ks], s_acc[t], 0, 0, 0);
+                    for (int x = 0; x < 16; ++x) s_acc[t][x] = 0.f;
+                }
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[st & 1][x]), q_reg[half * 4 + x],
+                                                                      s_acc[t], 0, 0, 0);
+                STEM_SCHED_FENCE();
             }
         }
         STEM_BARRIER();                                // every wave is done with K(j)
-        if (has_next)
-            request_block<B, false>(k_head, kv_st, seq_lo + list[it_next] * B, seq_hi, k_lds, w, lane);
+        const auto k_rq = k_request(has_next ? list[it_next] : j);   // issued inside O^T (if has_next)
 
         // ---- causal mask inside the diagonal block: accumulator x of tile t is key
-        //      t*32 + 16*(x/8) + 8*hi + x%8 of the block ----
+        //      t*32 + 16*(x/8) + 8*hi + x%8 of the block.  The limit is written in terms of j so
+        //      that the 64 comparisons are made here, not hoisted out of the block loop ----
         if (diag) {
+            const int limit = qrow - 8 * hi + (i - j);
 #pragma unroll
             for (int t = 0; t < KT; ++t)
 #pragma unroll
-                for (int x = 0; x < 16; ++x) {
-                    const int key = t * 32 + 16 * (x >> 3) + 8 * hi + (x & 7);
-                    if (key > qrow) s_acc[t][x] = neg_inf;
-                }
+                for (int x = 0; x < 16; ++x)
+                    if (t * 32 + 16 * (x >> 3) + (x & 7) > limit) s_acc[t][x] = neg_inf;
         }
 
-        // ---- online softmax; the reference only moves when the block maximum exceeds it by
-        //      more than 2^8 in the exp2 domain, so rescaling O is rare ----
-        float mx = s_acc[0][0];
-#pragma unroll
-        for (int t = 0; t < KT; ++t)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) mx = fmaxf(mx, s_acc[t][x]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const bool move = (mx - m_ref) * sl2 > 8.0f || m_ref == neg_inf;
-        if (__builtin_amdgcn_ballot_w64(move && mx > neg_inf) != 0) {
-            const float m_new = (move && mx > neg_inf) ? mx : m_ref;
-            const float corr = (m_ref == neg_inf) ? 0.f : __builtin_amdgcn_exp2f((m_ref - m_new) * sl2);
-            m_ref = m_new;
-            l_run *= corr;
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) o_acc[dt][x] *= corr;
-        }
-        const float off = (m_ref == neg_inf) ? 0.f : m_ref * sl2;
-        float psum = 0.f;
+        // ---- online softmax, exp2 domain.  p = exp2((s - m_ref) * sl2) with a per-query reference
+        //      m_ref that is NOT the running maximum: it is set from the first block's maximum and
+        //      moved only when a block would overflow, so the common case needs no row maximum and
+        //      no rescaling of O.  The row sum adds the bf16-rounded probabilities (the very values
+        //      the second product uses), two per v_dot2c_f32_bf16. ----
         uint32_t p_pk[KT][8];                          // bf16 pairs: [tile][16-key step * 4 + pair]
+        float psum = 0.f;
+        auto probabilities = [&]() {
+            const float off = m_ref * sl2;
+            float ps[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int t = 0; t < KT; ++t)
+            for (int t = 0; t < KT; ++t)
 #pragma unroll
-            for (int x = 0; x < 16; x += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(s_acc[t][x] * sl2 - off);
-                const float p1 = __builtin_amdgcn_exp2f(s_acc[t][x + 1] * sl2 - off);
-                psum += p0 + p1;
-                p_pk[t][x >> 1] = pack_bf16(p0, p1);
+                for (int x = 0; x < 16; x += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(s_acc[t][x] * sl2 - off);
+                    const float p1 = __builtin_amdgcn_exp2f(s_acc[t][x + 1] * sl2 - off);
+                    const uint32_t pk = pack_bf16(p0, p1);
+                    p_pk[t][x >> 1] = pk;
+                    ps[(x >> 1) & 3] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk),
+                                                                       __builtin_bit_cast(bf16x2_t, 0x3f803f80u),
+                                                                       ps[(x >> 1) & 3], false);
+                }
+            psum = (ps[0] + ps[1]) + (ps[2] + ps[3]);
+        };
+        bool redo = first_block;
+        if (!first_block) {
+            probabilities();
+            // a sum that is not a modest finite number (a probability above 2^16, inf) means the
+            // reference is too low for this block
+            redo = __builtin_amdgcn_ballot_w64(!(psum <= 65536.0f)) != 0;
+        }
+        if (redo) {
+            float mx4[4] = {s_acc[0][0], s_acc[0][1], s_acc[0][2], s_acc[0][3]};
+#pragma unroll
+            for (int t = 0; t < KT; ++t)
+#pragma unroll
+                for (int x = 0; x < 16; ++x) mx4[x & 3] = fmaxf(mx4[x & 3], s_acc[t][x]);
+            float mx = fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3]));
+            {
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));   // both halves of the query
             }
+            if (mx > m_ref) {                          // same decision in both lanes of a query
+                const float corr = (m_ref == neg_inf) ? 0.f : __builtin_amdgcn_exp2f((m_ref - mx) * sl2);
+                m_ref = mx;
+                l_run *= corr;
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                    for (int x = 0; x < 16; ++x) o_acc[dt][x] *= corr;
+            }
+            if (m_ref == neg_inf) m_ref = 0.f;         // nothing visible yet: any finite reference
+            probabilities();
+            first_block = false;
+        }
         l_run += psum;
 
-        if (has_next) STEM_WAIT_VMCNT(8); else STEM_WAIT_VMCNT(0);
+        STEM_WAIT_VMCNT(0);
         STEM_BARRIER();                                // V(j) is in LDS
 
-        // ---- O^T += V^T P^T ----
+        // ---- O^T += V^T P^T : KT*2 steps of 16 keys ----
+        {
+            uint4 va[2][4];
+            load_v_step(0, va[0]);
+            STEM_SCHED_FENCE();
 #pragma unroll
-        for (int t = 0; t < KT; ++t)
+            for (int st = 0; st < KT * 2; ++st) {
+                if (st + 1 < KT * 2) load_v_step(st + 1, va[(st + 1) & 1]);
+                if (has_next && st < kRequestGroups) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+                    for (int x = 0; x < 8 / kRequestGroups; ++x) k_rq.issue(st * (8 / kRequestGroups) + x, k_slice0);
+                }
+                STEM_SCHED_FENCE();
+                const int t = st >> 1, u = st & 1;
                 const uint4 pb = make_uint4(p_pk[t][u * 4], p_pk[t][u * 4 + 1], p_pk[t][u * 4 + 2],
                                             p_pk[t][u * 4 + 3]);
-                const unsigned char* rowp = v_lds + (t * 32 + 16 * u + v_row) * kRowBytes + v_in;
 #pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    const unsigned char* p0 = rowp + ((dt ^ v_swz) << 6);
-                    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)p0);
-                    const s16x4_t hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p0 + 4 * kRowBytes));
-                    const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi4);
-                    const uint4 a = make_uint4(lo2.x, lo2.y, hi2.x, hi2.y);
-                    o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(pb), o_acc[dt], 0, 0, 0);
-                }
+                for (int dt = 0; dt < 4; ++dt)
+                    o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[st & 1][dt]), as_bf16x8(pb),
+                                                                       o_acc[dt], 0, 0, 0);
+                STEM_SCHED_FENCE();
             }
+        }
         it = it_next;
     }
 
     // ---- normalise and store: accumulator x of d tile dt is column dt*32 + 8*(x/4) + 4*hi + x%4 ----
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    float l_tot;
+    {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
+        l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+    }
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     if (q_valid) {
         uint16_t* dst = out + (int64_t)tok_q * q_st + (int64_t)h * q_sh + hi * 4;

@@ -70,7 +70,7 @@ def full_size_case(w, n_random_rows, heads):
                     o_out[lo + i * B:min(lo + (i + 1) * B, hi), h] = np.nan
     max_abs, rel_l2 = pu.check_output(pf.out, o_out, w.name)
     m = ~np.isnan(o_lse)
-    assert np.abs(pf.lse.cpu().numpy()[m] - o_lse[m]).max() <= 2e-3
+    assert np.abs(pf.lse.cpu().numpy()[m] - o_lse[m]).max() <= 5e-3
     # whole-output invariants
     assert not torch.isnan(pf.out).any().item()
     G = w.num_q_heads // w.num_kv_heads

@@ -64,7 +64,7 @@ def run_both(w, rows=None, heads=None):
                     o_lse[h, lo + i * B:min(lo + (i + 1) * B, hi)] = np.nan
     max_abs, rel_l2 = pu.check_output(pf.out, o_out, w.name)
     m = ~np.isnan(o_lse)
-    assert np.abs(g_lse[m] - o_lse[m]).max() <= 2e-3
+    assert np.abs(g_lse[m] - o_lse[m]).max() <= 5e-3
     say("%s: score err %.3g, out max-abs %.4g rel-L2 %.4g" % (w.name, err, max_abs, rel_l2))
     return pf, data, qkv, (counts, indices)
 
@@ -139,7 +139,7 @@ def test_attention_on_given_lists_full_budget_and_random():
         torch.cuda.synchronize()
         o_out, o_lse = so.sparse_attention(*qkv, cu, B, counts, idx, w.softmax_scale)
         pu.check_output(out, o_out, mode)
-        assert np.abs(lse.cpu().numpy() - o_lse).max() <= 2e-3
+        assert np.abs(lse.cpu().numpy() - o_lse).max() <= 5e-3
 
 
 def test_outputs_are_deterministic_and_strided_views_work():
