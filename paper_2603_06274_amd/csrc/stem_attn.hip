@@ -115,9 +115,6 @@ __device__ __forceinline__ void sparse_attn_body(
     int T, int kmax, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh, float scale,
     int items_per_xcd, unsigned char* __restrict__ k_lds, unsigned char* __restrict__ v_lds) {
     constexpr int KT = B / 32;                         // 32-key tiles per block
-    // the 8 slice requests of a block go out over the first kRequestGroups groups of 4 matrix
-    // instructions of a phase (a phase has KT*2 groups)
-    constexpr int kRequestGroups = (KT * 2 >= 8) ? 4 : KT * 2;
 
     // ---- which (head, row): consecutive workgroup ids go to different XCDs, so give every XCD a
     // contiguous range of the (kv head, row descending, head in group) order ----
@@ -166,11 +163,13 @@ __device__ __forceinline__ void sparse_attn_body(
     unsigned char* k_slice0 = k_lds + w * 1024;        // this wave's first request slice
     unsigned char* v_slice0 = v_lds + w * 1024;
 
-    // first usable list entry (entries outside 0..i are skipped)
-    int it = 0;
-    while (it < cnt && (list[it] < 0 || list[it] > i)) ++it;
-    if (it < cnt) {
-        const auto rq = k_request(list[it]);
+    // List entries outside 0..i break the precondition; they are processed as fully masked
+    // blocks (clamped for addressing), which costs time but keeps the control flow flat.
+    auto usable = [&](int j) { return j >= 0 && j <= i; };
+    auto clamped = [&](int j) { return min(max(j, 0), i); };
+    int j_cur = cnt > 0 ? list[0] : 0;
+    if (cnt > 0) {
+        const auto rq = k_request(clamped(j_cur));
 #pragma unroll
         for (int u = 0; u < 8; ++u) rq.issue(u, k_slice0);
     }
@@ -207,12 +206,11 @@ __device__ __forceinline__ void sparse_attn_body(
     const int v_swz = v_row & 3;                       // key0 and the +4 keep (row & 3)
     const unsigned char* v_rd = v_lds + v_row * kRowBytes + (((lane >> 4) & 1) << 5) + ((lane & 3) << 3);
 
-    // operand fetches, written so that the next group of LDS reads is issued before the matrix
-    // instructions of the current group
-    auto load_k_half = [&](int t, int half, uint4* dst) {
+    auto load_k_group = [&](int grp, uint4* dst) {     // operands of matrix instructions 4*grp .. 4*grp+3 of S^T
+        const int t = grp >> 1, part = grp & 1;
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
-            const int c = (half * 4 + x) * 2 + hi;
+            const int c = (part * 4 + x) * 2 + hi;
             dst[x] = *reinterpret_cast<const uint4*>(k_rd + t * 32 * kRowBytes + ((c ^ k_swz) << 4));
         }
     };
@@ -227,143 +225,188 @@ __device__ __forceinline__ void sparse_attn_body(
         }
     };
 
+    // The block's keys are handled as two halves (tiles [0, HT) and [HT, KT)) so that, inside one
+    // wave's instruction stream, the softmax of one half is issued between the matrix instructions
+    // of the other: vector and matrix instructions of the SAME wave overlap well, those of two
+    // waves sharing a SIMD do not.
+    constexpr int HT = KT / 2;                         // tiles per half
+    constexpr int HG = HT * 2;                         // groups of 4 matrix instructions per half and product
+    f32x16_t s_acc[KT];
+    uint32_t p_pk[KT][8];                              // bf16 pairs: [tile][16-key step * 4 + pair]
+    float ps[2][4];                                    // row-sum partials of the two halves
+
+    // softmax of one accumulator pair (tile t, elements x, x+1): exp2 domain, reference m_ref,
+    // packed to bf16, summed from the rounded values with one v_dot2c_f32_bf16
+    auto softmax_pair = [&](int half, int t, int x, float off) {
+        const float p0 = __builtin_amdgcn_exp2f(s_acc[t][x] * sl2 - off);
+        const float p1 = __builtin_amdgcn_exp2f(s_acc[t][x + 1] * sl2 - off);
+        const uint32_t pk = pack_bf16(p0, p1);
+        p_pk[t][x >> 1] = pk;
+        ps[half][(x >> 1) & 3] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk),
+                                                                 __builtin_bit_cast(bf16x2_t, 0x3f803f80u),
+                                                                 ps[half][(x >> 1) & 3], false);
+    };
+    auto half_sum = [&](int half) { return (ps[half][0] + ps[half][1]) + (ps[half][2] + ps[half][3]); };
+    // Slow path of the softmax for one half: take the true maximum, move the reference up to it
+    // (rescaling O and l), and recompute the half's probabilities.
+    auto fix_half = [&](int half) {
+        float mx4[4] = {neg_inf, neg_inf, neg_inf, neg_inf};
+#pragma unroll
+        for (int t = half * HT; t < (half + 1) * HT; ++t)
+#pragma unroll
+            for (int x = 0; x < 16; ++x) mx4[x & 3] = fmaxf(mx4[x & 3], s_acc[t][x]);
+        float mx = fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3]));
+        {
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+            mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));   // both lanes of the query
+        }
+        if (mx > m_ref) {
+            const float corr = (m_ref == neg_inf) ? 0.f : __builtin_amdgcn_exp2f((m_ref - mx) * sl2);
+            m_ref = mx;
+            l_run *= corr;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int x = 0; x < 16; ++x) o_acc[dt][x] *= corr;
+        }
+        if (m_ref == neg_inf) m_ref = 0.f;             // nothing visible yet: any finite reference
+        const float off = m_ref * sl2;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ps[half][e] = 0.f;
+#pragma unroll
+        for (int t = half * HT; t < (half + 1) * HT; ++t)
+#pragma unroll
+            for (int x = 0; x < 16; x += 2) softmax_pair(half, t, x, off);
+    };
+    // a sum that is not a modest finite number (a probability above 2^16, inf, NaN) means the
+    // reference is too low for this half
+    auto overflowed = [&](float sum) { return __builtin_amdgcn_ballot_w64(!(sum <= 65536.0f)) != 0; };
+    auto mask_half = [&](int half, int limit) {
+#pragma unroll
+        for (int t = half * HT; t < (half + 1) * HT; ++t)
+#pragma unroll
+            for (int x = 0; x < 16; ++x)
+                if (t * 32 + 16 * (x >> 3) + (x & 7) > limit) s_acc[t][x] = neg_inf;
+    };
+
     bool first_block = true;
-    while (it < cnt) {
-        const int j = list[it];
-        int it_next = it + 1;
-        while (it_next < cnt && (list[it_next] < 0 || list[it_next] > i)) ++it_next;
-        const bool has_next = it_next < cnt;
-        const bool diag = (j == i);
+    for (int it = 0; it < cnt; ++it) {
+        const int j = clamped(j_cur);
+        const bool has_next = it + 1 < cnt;
+        const int j_nxt = has_next ? list[it + 1] : 0;  // scalar load, consumed after S^T
+        // accumulator x of tile t is key t*32 + 16*(x/8) + 8*hi + x%8 of the block: on the diagonal
+        // block keys above the query are masked; an unusable entry is masked entirely
+        const bool masked = (j == i) || !usable(j_cur);
+        const int mask_limit = usable(j_cur) ? qrow - 8 * hi + (i - j) : -1;
 
         STEM_WAIT_VMCNT(0);
         STEM_BARRIER();                                // K(j) is in LDS; V buffer is free
-        const auto v_rq = v_request(j);                // issued two slices at a time inside S^T
+        const auto v_rq = v_request(j);
 
-        // ---- S^T = K Q^T : KT tiles of 32 keys x 32 queries ----
-        f32x16_t s_acc[KT];
-        {
-            uint4 ka[2][4];
-            load_k_half(0, 0, ka[0]);
+        // ---- S^T, first half, with the V requests in between ----
+        uint4 ka[2][4];
+        load_k_group(0, ka[0]);
+        STEM_SCHED_FENCE();
+#pragma unroll
+        for (int grp = 0; grp < HG; ++grp) {
+            load_k_group(grp + 1, ka[(grp + 1) & 1]);
+#pragma unroll
+            for (int x = 0; x < 8 / HG; ++x) v_rq.issue(grp * (8 / HG) + x, v_slice0);
             STEM_SCHED_FENCE();
+            const int t = grp >> 1, part = grp & 1;
+            if (part == 0) {
 #pragma unroll
-            for (int st = 0; st < KT * 2; ++st) {
-                const int t = st >> 1, half = st & 1;
-                if (st + 1 < KT * 2) load_k_half((st + 1) >> 1, (st + 1) & 1, ka[(st + 1) & 1]);
-                if (st < kRequestGroups) {
+                for (int x = 0; x < 16; ++x) s_acc[t][x] = 0.f;
+            }
 #pragma unroll
-                    for (int x = 0; x < 8 / kRequestGroups; ++x) v_rq.issue(st * (8 / kRequestGroups) + x, v_slice0);
-                }
+            for (int x = 0; x < 4; ++x)
+                s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[grp & 1][x]), q_reg[part * 4 + x],
+                                                                  s_acc[t], 0, 0, 0);
+            STEM_SCHED_FENCE();
+        }
+        if (masked) mask_half(0, mask_limit);
+
+        // ---- S^T, second half, one matrix instruction per step, with the first half's softmax
+        //      (one accumulator pair per step) issued in its shadow ----
+        {
+            const float off = m_ref * sl2;             // -inf on the first block: redone below
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ps[0][e] = 0.f;
+#pragma unroll
+            for (int grp = HG; grp < 2 * HG; ++grp) {
+                if (grp + 1 < 2 * HG) load_k_group(grp + 1, ka[(grp + 1) & 1]);
                 STEM_SCHED_FENCE();
-                if (half == 0) {
+                const int t = grp >> 1, part = grp & 1;
+                if (part == 0) {
 #pragma unroll
                     for (int x = 0; x < 16; ++x) s_acc[t][x] = 0.f;
                 }
 #pragma unroll
-                for (int x = 0; x < 4; ++x)
-                    s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[st & 1][x]), q_reg[half * 4 + x],
+                for (int x = 0; x < 4; ++x) {
+                    s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[grp & 1][x]), q_reg[part * 4 + x],
                                                                       s_acc[t], 0, 0, 0);
-                STEM_SCHED_FENCE();
+                    const int n = (grp - HG) * 4 + x;  // softmax step: pair n of the first half
+                    softmax_pair(0, n >> 3, (n & 7) * 2, off);
+                    STEM_SCHED_FENCE();
+                }
             }
         }
         STEM_BARRIER();                                // every wave is done with K(j)
-        const auto k_rq = k_request(has_next ? list[it_next] : j);   // issued inside O^T (if has_next)
-
-        // ---- causal mask inside the diagonal block: accumulator x of tile t is key
-        //      t*32 + 16*(x/8) + 8*hi + x%8 of the block.  The limit is written in terms of j so
-        //      that the 64 comparisons are made here, not hoisted out of the block loop ----
-        if (diag) {
-            const int limit = qrow - 8 * hi + (i - j);
-#pragma unroll
-            for (int t = 0; t < KT; ++t)
-#pragma unroll
-                for (int x = 0; x < 16; ++x)
-                    if (t * 32 + 16 * (x >> 3) + (x & 7) > limit) s_acc[t][x] = neg_inf;
-        }
-
-        // ---- online softmax, exp2 domain.  p = exp2((s - m_ref) * sl2) with a per-query reference
-        //      m_ref that is NOT the running maximum: it is set from the first block's maximum and
-        //      moved only when a block would overflow, so the common case needs no row maximum and
-        //      no rescaling of O.  The row sum adds the bf16-rounded probabilities (the very values
-        //      the second product uses), two per v_dot2c_f32_bf16. ----
-        uint32_t p_pk[KT][8];                          // bf16 pairs: [tile][16-key step * 4 + pair]
-        float psum = 0.f;
-        auto probabilities = [&]() {
-            const float off = m_ref * sl2;
-            float ps[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int t = 0; t < KT; ++t)
-#pragma unroll
-                for (int x = 0; x < 16; x += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(s_acc[t][x] * sl2 - off);
-                    const float p1 = __builtin_amdgcn_exp2f(s_acc[t][x + 1] * sl2 - off);
-                    const uint32_t pk = pack_bf16(p0, p1);
-                    p_pk[t][x >> 1] = pk;
-                    ps[(x >> 1) & 3] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk),
-                                                                       __builtin_bit_cast(bf16x2_t, 0x3f803f80u),
-                                                                       ps[(x >> 1) & 3], false);
-                }
-            psum = (ps[0] + ps[1]) + (ps[2] + ps[3]);
-        };
-        bool redo = first_block;
-        if (!first_block) {
-            probabilities();
-            // a sum that is not a modest finite number (a probability above 2^16, inf) means the
-            // reference is too low for this block
-            redo = __builtin_amdgcn_ballot_w64(!(psum <= 65536.0f)) != 0;
-        }
-        if (redo) {
-            float mx4[4] = {s_acc[0][0], s_acc[0][1], s_acc[0][2], s_acc[0][3]};
-#pragma unroll
-            for (int t = 0; t < KT; ++t)
-#pragma unroll
-                for (int x = 0; x < 16; ++x) mx4[x & 3] = fmaxf(mx4[x & 3], s_acc[t][x]);
-            float mx = fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3]));
-            {
-                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));   // both halves of the query
-            }
-            if (mx > m_ref) {                          // same decision in both lanes of a query
-                const float corr = (m_ref == neg_inf) ? 0.f : __builtin_amdgcn_exp2f((m_ref - mx) * sl2);
-                m_ref = mx;
-                l_run *= corr;
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                    for (int x = 0; x < 16; ++x) o_acc[dt][x] *= corr;
-            }
-            if (m_ref == neg_inf) m_ref = 0.f;         // nothing visible yet: any finite reference
-            probabilities();
-            first_block = false;
-        }
-        l_run += psum;
+        const auto k_rq = k_request(clamped(j_nxt));   // issued inside the first part of O^T (if has_next)
+        if (masked) mask_half(1, mask_limit);
+        if (first_block || overflowed(half_sum(0))) fix_half(0);
+        first_block = false;
+        l_run += half_sum(0);
 
         STEM_WAIT_VMCNT(0);
         STEM_BARRIER();                                // V(j) is in LDS
 
-        // ---- O^T += V^T P^T : KT*2 steps of 16 keys ----
+        // ---- O^T, first half of the keys, with the second half's softmax in its shadow and the
+        //      next block's K requests in between ----
+        uint4 va[2][4];
+        load_v_step(0, va[0]);
+        STEM_SCHED_FENCE();
         {
-            uint4 va[2][4];
-            load_v_step(0, va[0]);
-            STEM_SCHED_FENCE();
+            const float off = m_ref * sl2;
 #pragma unroll
-            for (int st = 0; st < KT * 2; ++st) {
-                if (st + 1 < KT * 2) load_v_step(st + 1, va[(st + 1) & 1]);
-                if (has_next && st < kRequestGroups) {
+            for (int e = 0; e < 4; ++e) ps[1][e] = 0.f;
 #pragma unroll
-                    for (int x = 0; x < 8 / kRequestGroups; ++x) k_rq.issue(st * (8 / kRequestGroups) + x, k_slice0);
+            for (int g2 = 0; g2 < HG; ++g2) {
+                load_v_step(g2 + 1, va[(g2 + 1) & 1]);
+                if (has_next) {
+#pragma unroll
+                    for (int x = 0; x < 8 / HG; ++x) k_rq.issue(g2 * (8 / HG) + x, k_slice0);
                 }
                 STEM_SCHED_FENCE();
-                const int t = st >> 1, u = st & 1;
-                const uint4 pb = make_uint4(p_pk[t][u * 4], p_pk[t][u * 4 + 1], p_pk[t][u * 4 + 2],
-                                            p_pk[t][u * 4 + 3]);
+                const int t = g2 >> 1, u = g2 & 1;
+                const uint4 pb = make_uint4(p_pk[t][u * 4], p_pk[t][u * 4 + 1], p_pk[t][u * 4 + 2], p_pk[t][u * 4 + 3]);
 #pragma unroll
-                for (int dt = 0; dt < 4; ++dt)
-                    o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[st & 1][dt]), as_bf16x8(pb),
+                for (int dt = 0; dt < 4; ++dt) {
+                    o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[g2 & 1][dt]), as_bf16x8(pb),
                                                                        o_acc[dt], 0, 0, 0);
-                STEM_SCHED_FENCE();
+                    const int n = g2 * 4 + dt;         // softmax step: pair n of the second half
+                    softmax_pair(1, HT + (n >> 3), (n & 7) * 2, off);
+                    STEM_SCHED_FENCE();
+                }
             }
         }
-        it = it_next;
+        if (overflowed(half_sum(1))) fix_half(1);
+        l_run += half_sum(1);
+
+        // ---- O^T, second half of the keys ----
+#pragma unroll
+        for (int g2 = HG; g2 < 2 * HG; ++g2) {
+            if (g2 + 1 < 2 * HG) load_v_step(g2 + 1, va[(g2 + 1) & 1]);
+            STEM_SCHED_FENCE();
+            const int t = g2 >> 1, u = g2 & 1;
+            const uint4 pb = make_uint4(p_pk[t][u * 4], p_pk[t][u * 4 + 1], p_pk[t][u * 4 + 2], p_pk[t][u * 4 + 3]);
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+                o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[g2 & 1][dt]), as_bf16x8(pb),
+                                                                   o_acc[dt], 0, 0, 0);
+            STEM_SCHED_FENCE();
+        }
+        j_cur = j_nxt;
     }
 
     // ---- normalise and store: accumulator x of d tile dt is column dt*32 + 8*(x/4) + 4*hi + x%4 ----
