@@ -26,9 +26,10 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
-# HBM bytes per sparse-attention launch on the 128K layer, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this script (see profiles/); None until measured.
-MEASURED_ATTN_TRAFFIC_BYTES = None
+# HBM-side bytes per sparse-attention launch on the 128K layer, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this script (profiles/sparse_attn_kernel_llama8b_128k.md): FETCH_SIZE
+# 6.894e6 KiB x 2.0 (copy calibration) + WRITE_SIZE 1.049e6 KiB x 1.0.  Only valid for that workload.
+MEASURED_ATTN_TRAFFIC_BYTES = {"llama8b_128k": 15.2e9}
 
 
 def median(xs):
@@ -170,7 +171,7 @@ def main():
         "attention_dense_equiv_tflops": round(dense_flops / (t_attn_avg * 1e-3) / 1e12, 2),
         "roofline": {"kernel": "sparse_attn_kernel", "bound": "mfma", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_ATTN_TRAFFIC_BYTES},
+                     "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(w.name)},
         "estimate_roofline": {"kernel": "pool_kernel", "bound": "hbm", "achieved": round(pool_gbs, 1),
                               "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(pool_gbs / PEAK_HBM_GBS, 4),
                               "algorithmic_bytes": pool_bytes},
