@@ -54,7 +54,7 @@ def cpu_baseline(w, data, dense_flops):
     budget = so.packed_budget(w.cu_seqlens, w.block_size, w.k_start_blocks, w.mu, w.k_min, w.n_sink, w.n_local)
     counts, indices = so.select_blocks(scores, budget, w.cu_seqlens, w.block_size, w.n_sink, w.n_local)
     t12 = time.perf_counter() - t0
-    n_rows = 48
+    n_rows = 512
     rows = [int(x) for x in np.linspace(0, w.total_rows - 1, n_rows)]
     t0 = time.perf_counter()
     so.sparse_attention(q, k, v, w.cu_seqlens, w.block_size, counts, indices, w.softmax_scale, rows=rows)
