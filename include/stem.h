@@ -137,7 +137,9 @@ int stem_select(const stem_shape* shape, const float* scores, const int32_t* bud
  * lse (device fp32 [Hq, T], may be NULL) receives log sum_u exp(softmax_scale * <Q,K>) per query.
  * Any list is accepted, not only stem_select's, provided each row's list is ascending, causal
  * (entries <= i) and holds the diagonal block i.  Lists are not validated: entries outside 0..i
- * are skipped (never an out-of-bounds access); a row with no usable entry yields zeros.
+ * contribute nothing (they cost the time of a block, never an out-of-bounds access); a row with
+ * no usable entry yields zeros.  STEM_ERR_UNSUPPORTED if one sequence of one KV head spans 2 GiB
+ * or more, i.e. (tokens - 1) * kv_stride_token * 2 + 256 bytes > 2^31 - 1.
  */
 int stem_sparse_attn(const stem_shape* shape, const void* q, const void* k, const void* v,
                      const int32_t* counts, const int32_t* indices, int32_t kmax,

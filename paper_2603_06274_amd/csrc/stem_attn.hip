@@ -12,11 +12,17 @@
 // order (bits 2 and 3 of the row index swapped) that makes each lane's eight accumulator values of
 // a 16-key step eight consecutive keys.
 //
-// K and V blocks go from global memory straight into LDS (global_load_lds_dwordx4, no staging
-// registers), one buffer each, refilled in split phases: the next K block is requested as soon as
-// every wave has finished S^T and lands while softmax and O^T run; the V block is requested at
-// the top of the iteration and lands while S^T and softmax run.  Two workgroups share a CU, so one
-// workgroup's matrix work overlaps the other's softmax and waits.
+// K and V blocks go from global memory straight into LDS (buffer_load ... lds, no staging
+// registers), one buffer each, refilled in split phases behind two barriers per block: the V block
+// is requested during the first half of S^T and must have landed when S^T ends; the next K block
+// is requested during O^T and must have landed when the next iteration starts.  Two workgroups
+// share a CU, so one workgroup's matrix work fills the other's waits.
+//
+// Inside a wave the instruction stream is kept dense around the matrix instructions: LDS operands
+// are read six matrix instructions ahead into a ring of registers, the softmax of a block is
+// spread pair by pair over the wave's own matrix instructions (S^T tiles 1..3 and the first three
+// quarters of O^T), and the softmax runs without a running maximum: a per-query reference is set
+// on the first block and moved only when a window of probabilities overflows (slow path).
 //
 // LDS layouts (256-byte rows): K has its 16-byte chunks XORed with (row & 15), so the 32 rows a
 // b128 operand read touches spread over all banks; V has its 64-byte groups XORed with (row & 3),
@@ -56,6 +62,17 @@ __device__ __forceinline__ int swap_bits_2_3(int x) {
 // s_waitcnt with only vmcnt set (gfx9 encoding: vmcnt[3:0], expcnt[6:4]=7, lgkmcnt[11:8]=15); the
 // builtin, unlike inline asm, is seen by the compiler's own wait-count bookkeeping.
 #define STEM_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | (N))
+// the same with only lgkmcnt set (vmcnt is split over bits [3:0] and [15:14])
+#define STEM_WAIT_LGKMCNT_CASE(N) case N: __builtin_amdgcn_s_waitcnt(0xC07F | ((N) << 8)); break;
+__device__ __forceinline__ void wait_lgkmcnt(int n) {   // n is a constant after unrolling: the switch folds away
+    switch (n) {
+        STEM_WAIT_LGKMCNT_CASE(0) STEM_WAIT_LGKMCNT_CASE(1) STEM_WAIT_LGKMCNT_CASE(2) STEM_WAIT_LGKMCNT_CASE(3)
+        STEM_WAIT_LGKMCNT_CASE(4) STEM_WAIT_LGKMCNT_CASE(5) STEM_WAIT_LGKMCNT_CASE(6) STEM_WAIT_LGKMCNT_CASE(7)
+        STEM_WAIT_LGKMCNT_CASE(8) STEM_WAIT_LGKMCNT_CASE(9) STEM_WAIT_LGKMCNT_CASE(10) STEM_WAIT_LGKMCNT_CASE(11)
+        STEM_WAIT_LGKMCNT_CASE(12) STEM_WAIT_LGKMCNT_CASE(13) STEM_WAIT_LGKMCNT_CASE(14)
+        default: break;
+    }
+}
 
 // Nothing is scheduled across this point: keeps the next group of LDS operand reads ahead of the
 // matrix instructions that consume the current group.
@@ -65,43 +82,33 @@ constexpr int kRowBytes = kHeadDim * 2;               // one K or V row in LDS
 
 // One 1 KiB slice (4 rows) of a B x 128 bf16 block, global -> LDS.  A block is 8 slices per wave:
 // wave w issues slices u*NW + w, u = 0..7, so that the row's swizzle term does not depend on u (for
-// B = 64 it depends on the parity of u only).  Requests are issued one or two at a time between
-// groups of matrix instructions, never as a burst: the texture-address unit takes a wave's 1 KiB
-// request at 64 B/clk, and a wave that finds its queue full cannot issue anything else.
+// B = 64 it depends on the parity of u only).  Requests are issued one at a time between matrix
+// instructions, never as a burst: the texture-address unit takes a wave's 1 KiB request at
+// 64 B/clk, and a wave that finds its queue full cannot issue anything else.
 //
-// The loads use buffer addressing: a per-block resource whose base is the block's first row in
-// this KV head and whose size ends with the sequence's last row, so rows past the end of a
-// partial last block (and past the end of the tensor) are never read and arrive in LDS as zeros
-// (their keys are masked by causality, their values get weight 0).  The per-lane byte offset is
-// computed once per kernel; a slice costs one vector add.
+// The loads use buffer addressing with one resource per tensor and workgroup: its base is the
+// sequence's first row in this KV head and its size ends with the sequence's last row, so rows
+// past the end of a partial last block (and past the end of the tensor) are never read and arrive
+// in LDS as zeros (their keys are masked by causality, their values get weight 0).  A block is a
+// byte offset added to the per-lane offset (one vector add per block), a slice one more add.
 struct BlockRequest {
     __amdgpu_buffer_rsrc_t rsrc;
-    uint32_t lane_off[2];           // per-lane byte offset for even / odd u
-    uint32_t slice_step;            // bytes between the rows of slices u and u+1 of one wave
+    uint32_t lane_off[2];           // block offset + per-lane byte offset, for even / odd u
 
-    __device__ __forceinline__ void issue(int u, unsigned char* __restrict__ slice0) const {
+    __device__ __forceinline__ void issue(int u, unsigned char* __restrict__ slice0, uint32_t slice_step,
+                                          int slice_lds_step) const {
         // slice0 = LDS address of this wave's slice for u = 0; slice u lies u*NW KiB further on
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_t*)(slice0 + u * (int)(slice_lds_step)), 16,
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_t*)(slice0 + u * slice_lds_step), 16,
                                                  lane_off[u & 1] + u * slice_step, 0, 0, 0);
     }
-    int slice_lds_step;
 };
 
-__device__ __forceinline__ BlockRequest make_request(const unsigned char* block_base, int rows_left,
-                                                     int64_t row_bytes, uint32_t off_even, uint32_t off_odd,
-                                                     int waves) {
-    BlockRequest rq;
-    // bytes from the block's first row to the end of the last existing row of this head
-    int64_t limit = (int64_t)(rows_left - 1) * row_bytes + kHeadDim * 2;
-    if (limit > 0xffffffffll) limit = 0xffffffffll;
-    // raw buffer (stride 0): num_records in bytes, loads beyond it return zero; 0x00020000 is the
-    // gfx9-family descriptor word for untyped 32-bit data
-    rq.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(block_base), 0, (int)(uint32_t)limit, 0x00020000);
-    rq.lane_off[0] = off_even;
-    rq.lane_off[1] = off_odd;
-    rq.slice_step = (uint32_t)(waves * 4 * row_bytes);
-    rq.slice_lds_step = waves * 1024;
-    return rq;
+// raw buffer (stride 0): num_records in bytes, loads beyond it return zero; 0x00020000 is the
+// gfx9-family descriptor word for untyped 32-bit data
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t sequence_resource(const uint16_t* first_row, int rows,
+                                                                    int64_t row_bytes) {
+    const int64_t bytes = rows > 0 ? (int64_t)(rows - 1) * row_bytes + kHeadDim * 2 : 0;   // < 2^31 (host check)
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(first_row), 0, (int)bytes, 0x00020000);
 }
 
 // The body takes the two LDS buffers as __restrict__ parameters: once inlined, every access carries
@@ -147,18 +154,22 @@ __device__ __forceinline__ void sparse_attn_body(
     const int64_t row_bytes = kv_st * 2;
     const int lrow = w * 4 + (lane >> 4), pc = lane & 15;
     const uint32_t lane_row_off = (uint32_t)(lrow * row_bytes);
-    const uint32_t k_off_even = lane_row_off + ((pc ^ (lrow & 15)) << 4);
-    const uint32_t k_off_odd = (B == 128) ? k_off_even : lane_row_off + ((pc ^ ((lrow + 8) & 15)) << 4);
-    const uint32_t v_off = lane_row_off + ((pc ^ ((lrow & 3) << 2)) << 4);
-    auto k_request = [&](int j) {
-        const int tok0 = seq_lo + j * B;
-        return make_request(reinterpret_cast<const unsigned char*>(k_head + (int64_t)tok0 * kv_st), seq_hi - tok0,
-                            row_bytes, k_off_even, k_off_odd, B / 32);
+    uint32_t k_off_even = lane_row_off + ((pc ^ (lrow & 15)) << 4);
+    uint32_t k_off_odd = (B == 128) ? k_off_even : lane_row_off + ((pc ^ ((lrow + 8) & 15)) << 4);
+    uint32_t v_off = lane_row_off + ((pc ^ ((lrow & 3) << 2)) << 4);
+    const auto k_rsrc = sequence_resource(k_head + (int64_t)seq_lo * kv_st, seq_hi - seq_lo, row_bytes);
+    const auto v_rsrc = sequence_resource(v_head + (int64_t)seq_lo * kv_st, seq_hi - seq_lo, row_bytes);
+    const uint32_t block_bytes = (uint32_t)(B * row_bytes);
+    const uint32_t slice_step = (uint32_t)((B / 32) * 4 * row_bytes);   // rows of slices u and u+1 of one wave
+    constexpr int slice_lds_step = (B / 32) * 1024;
+    // !real: an offset beyond any sequence, so that nothing is fetched (zeros land in LDS)
+    auto k_request = [&](int j, bool real) {
+        const uint32_t off = real ? j * block_bytes : 0x80000000u;
+        return BlockRequest{k_rsrc, {k_off_even + off, k_off_odd + off}};
     };
     auto v_request = [&](int j) {
-        const int tok0 = seq_lo + j * B;
-        return make_request(reinterpret_cast<const unsigned char*>(v_head + (int64_t)tok0 * kv_st), seq_hi - tok0,
-                            row_bytes, v_off, v_off, B / 32);
+        const uint32_t off = j * block_bytes;
+        return BlockRequest{v_rsrc, {v_off + off, v_off + off}};
     };
     unsigned char* k_slice0 = k_lds + w * 1024;        // this wave's first request slice
     unsigned char* v_slice0 = v_lds + w * 1024;
@@ -167,11 +178,16 @@ __device__ __forceinline__ void sparse_attn_body(
     // blocks (clamped for addressing), which costs time but keeps the control flow flat.
     auto usable = [&](int j) { return j >= 0 && j <= i; };
     auto clamped = [&](int j) { return min(max(j, 0), i); };
-    int j_cur = cnt > 0 ? list[0] : 0;
+    // The list lives in a vector register, 64 entries at a time (lane e holds entry e of the
+    // chunk), and entries are taken out with v_readlane: no scalar load sits in the loop, so the
+    // in-order LDS operand reads are the only users of their counter there.
+    auto list_chunk = [&](int first) { return first + lane < cnt ? list[first + lane] : 0; };
+    int list_reg = list_chunk(0);
+    int j_cur = __builtin_amdgcn_readlane(list_reg, 0);
     if (cnt > 0) {
-        const auto rq = k_request(clamped(j_cur));
+        const auto rq = k_request(clamped(j_cur), true);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) rq.issue(u, k_slice0);
+        for (int u = 0; u < 8; ++u) rq.issue(u, k_slice0, slice_step, slice_lds_step);
     }
 
     // ---- Q rows of this wave as B operands: 8 k-steps of 16 along d ----
@@ -196,65 +212,91 @@ __device__ __forceinline__ void sparse_attn_body(
     float l_run = 0.f;                                 // this lane's share of the softmax sum
     const float sl2 = scale * 1.4426950408889634f;
 
-    // per-lane LDS addresses that do not change between blocks
+    // per-lane LDS offsets that do not change between blocks.  Both swizzles are XORs of address
+    // bits that are zero in the unswizzled per-lane offset, so the offset of operand n is one
+    // v_xor of a per-lane base with a constant, plus an immediate.
     const int k_row = swap_bits_2_3(col);              // + t*32 ; (row & 15) == (k_row & 15)
-    const unsigned char* k_rd = k_lds + k_row * kRowBytes;
-    const int k_swz = k_row & 15;
+    const uint32_t k_base0 = k_row * kRowBytes + (((k_row & 15) ^ hi) << 4);
     // transposing V read: lane l fetches row key0 + 8*hi + (l%16)/4 (+4), 8 bytes at column
     // dt*32 + 16*((l>>4)&1) + 4*(l&3); the 64-byte group index dt is XORed with (row & 3)
-    const int v_row = hi * 8 + ((lane & 15) >> 2);
-    const int v_swz = v_row & 3;                       // key0 and the +4 keep (row & 3)
-    const unsigned char* v_rd = v_lds + v_row * kRowBytes + (((lane >> 4) & 1) << 5) + ((lane & 3) << 3);
+    const int v_row = hi * 8 + ((lane & 15) >> 2);     // key0 and the +4 keep (row & 3)
+    const uint32_t v_base0 = v_row * kRowBytes + ((v_row & 3) << 6) + (((lane >> 4) & 1) << 5) + ((lane & 3) << 3);
+    uint32_t k_base = k_base0, v_base = v_base0;
 
-    auto load_k_group = [&](int grp, uint4* dst) {     // operands of matrix instructions 4*grp .. 4*grp+3 of S^T
-        const int t = grp >> 1, part = grp & 1;
-#pragma unroll
-        for (int x = 0; x < 4; ++x) {
-            const int c = (part * 4 + x) * 2 + hi;
-            dst[x] = *reinterpret_cast<const uint4*>(k_rd + t * 32 * kRowBytes + ((c ^ k_swz) << 4));
-        }
+    // Operand n of S^T (matrix instruction n: key tile n/8, 16-wide step n%8 along d; the lane's
+    // 16-byte chunk is 2*(n%8) + hi) and of O^T (matrix instruction n: 16-key step n/4, d tile n%4).
+    auto load_k = [&](int n) {
+        const int t = n >> 3;
+        return *reinterpret_cast<const uint4*>(k_lds + (k_base ^ ((n & 7) << 5)) + t * 32 * kRowBytes);
     };
-    auto load_v_step = [&](int step, uint4* dst) {     // step = 16 keys; 4 d tiles x 8 keys
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-            const unsigned char* p0 = v_rd + step * 16 * kRowBytes + ((dt ^ v_swz) << 6);
-            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)p0);
-            const s16x4_t up = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p0 + 4 * kRowBytes));
-            const uint2 lo2 = __builtin_bit_cast(uint2, lo), up2 = __builtin_bit_cast(uint2, up);
-            dst[dt] = make_uint4(lo2.x, lo2.y, up2.x, up2.y);
-        }
+    auto load_v = [&](int n) {
+        const int step = n >> 2, dt = n & 3;
+        const unsigned char* p0 = v_lds + (v_base ^ (dt << 6)) + step * 16 * kRowBytes;
+        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)p0);
+        const s16x4_t up = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p0 + 4 * kRowBytes));
+        const uint2 lo2 = __builtin_bit_cast(uint2, lo), up2 = __builtin_bit_cast(uint2, up);
+        return make_uint4(lo2.x, lo2.y, up2.x, up2.y);
     };
+    // Operands travel through a ring of kSlots registers, read kAhead matrix instructions before
+    // their use: the loaded LDS latency is several matrix instructions long.  They are consumed
+    // two at a time behind one wait (every instruction, waits included, takes an issue slot of
+    // the wave).  An O^T operand is two reads, and at most 15 reads can be counted in flight.
+    constexpr int kSlots = 8, kAhead = 6;
 
-    // The block's keys are handled as two halves (tiles [0, HT) and [HT, KT)) so that, inside one
-    // wave's instruction stream, the softmax of one half is issued between the matrix instructions
-    // of the other: vector and matrix instructions of the SAME wave overlap well, those of two
-    // waves sharing a SIMD do not.
-    constexpr int HT = KT / 2;                         // tiles per half
-    constexpr int HG = HT * 2;                         // groups of 4 matrix instructions per half and product
+    // The softmax of a block is 8*KT accumulator pairs per lane.  Vector and matrix instructions
+    // of the SAME wave overlap well, those of two waves sharing a SIMD do not, so the pairs are
+    // spread over the wave's own matrix instructions: slot s = 0 .. 2*NS-1 counts them (S^T first,
+    // then O^T), pair q = 8*t + x/2 may be issued once tile t of S^T is complete (slot 8t+7) and
+    // must be done before O^T reaches its 16 keys (slot NS + 8t + 4*((q%8)/4)).  For four tiles the
+    // pairs go out at two per three slots from slot 8 on, for two tiles at one per slot.
+    constexpr int NS = KT * 8;                         // matrix instructions per product and block
+    constexpr int NP = KT * 8;                         // accumulator pairs per block and lane
+    auto pairs_by = [](int slot) {                     // pairs issued once slot `slot` is issued
+        const int c = slot < 8 ? 0 : (KT == 4 ? ((slot - 7) * 2) / 3 : slot - 7);
+        return c > NP ? NP : c;
+    };
+    // The reference of the softmax can only be checked where a run of pairs is complete and not
+    // yet consumed: at these slot boundaries ("windows" of pairs between them).
+    constexpr int kChecks = KT == 4 ? 3 : 2;
+    constexpr int kCheckSlot[3] = {NS, KT == 4 ? 48 : 24, 56};
+
     f32x16_t s_acc[KT];
     uint32_t p_pk[KT][8];                              // bf16 pairs: [tile][16-key step * 4 + pair]
-    float ps[2][4];                                    // row-sum partials of the two halves
+    float ps[4];                                       // row-sum partials of the current window
+    float off;                                         // reference in exp2 units
 
-    // softmax of one accumulator pair (tile t, elements x, x+1): exp2 domain, reference m_ref,
+    // softmax of pair q (tile q/8, accumulators 2*(q%8) and +1): exp2 domain, reference m_ref,
     // packed to bf16, summed from the rounded values with one v_dot2c_f32_bf16
-    auto softmax_pair = [&](int half, int t, int x, float off) {
+    auto softmax_pair = [&](int q) {
+        const int t = q >> 3, x = (q & 7) * 2;
         const float p0 = __builtin_amdgcn_exp2f(s_acc[t][x] * sl2 - off);
         const float p1 = __builtin_amdgcn_exp2f(s_acc[t][x + 1] * sl2 - off);
-        const uint32_t pk = pack_bf16(p0, p1);
-        p_pk[t][x >> 1] = pk;
-        ps[half][(x >> 1) & 3] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk),
-                                                                 __builtin_bit_cast(bf16x2_t, 0x3f803f80u),
-                                                                 ps[half][(x >> 1) & 3], false);
+        uint32_t pk = pack_bf16(p0, p1);
+        float sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk),
+                                                    __builtin_bit_cast(bf16x2_t, 0x3f803f80u), ps[q & 3], false);
+        // An opaque use of the results at this point of the instruction stream: without it the
+        // compiler gathers the softmax next to the consumer of the results instead of leaving
+        // each pair next to "its" matrix instruction.
+        asm volatile("" : "+v"(pk), "+v"(sum));
+        p_pk[t][q & 7] = pk;
+        ps[q & 3] = sum;
     };
-    auto half_sum = [&](int half) { return (ps[half][0] + ps[half][1]) + (ps[half][2] + ps[half][3]); };
-    // Slow path of the softmax for one half: take the true maximum, move the reference up to it
-    // (rescaling O and l), and recompute the half's probabilities.
-    auto fix_half = [&](int half) {
+    auto softmax_slot = [&](int slot) {                // at most one pair per slot
+        if (pairs_by(slot) > pairs_by(slot - 1)) softmax_pair(pairs_by(slot - 1));
+    };
+    auto window_sum = [&]() { return (ps[0] + ps[1]) + (ps[2] + ps[3]); };
+    auto clear_sum = [&]() {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ps[e] = 0.f;
+    };
+    // Slow path for the window of pairs [q_lo, q_hi): take their true maximum, move the reference
+    // up to it (rescaling O and l), and recompute the window's probabilities.
+    auto fix_window = [&](int q_lo, int q_hi) {
         float mx4[4] = {neg_inf, neg_inf, neg_inf, neg_inf};
 #pragma unroll
-        for (int t = half * HT; t < (half + 1) * HT; ++t)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) mx4[x & 3] = fmaxf(mx4[x & 3], s_acc[t][x]);
+        for (int q = q_lo; q < q_hi; ++q) {
+            mx4[q & 3] = fmaxf(mx4[q & 3], fmaxf(s_acc[q >> 3][(q & 7) * 2], s_acc[q >> 3][(q & 7) * 2 + 1]));
+        }
         float mx = fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3]));
         {
             const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
@@ -270,144 +312,116 @@ __device__ __forceinline__ void sparse_attn_body(
                 for (int x = 0; x < 16; ++x) o_acc[dt][x] *= corr;
         }
         if (m_ref == neg_inf) m_ref = 0.f;             // nothing visible yet: any finite reference
-        const float off = m_ref * sl2;
+        off = m_ref * sl2;
+        clear_sum();
 #pragma unroll
-        for (int e = 0; e < 4; ++e) ps[half][e] = 0.f;
-#pragma unroll
-        for (int t = half * HT; t < (half + 1) * HT; ++t)
-#pragma unroll
-            for (int x = 0; x < 16; x += 2) softmax_pair(half, t, x, off);
+        for (int q = q_lo; q < q_hi; ++q) softmax_pair(q);
     };
     // a sum that is not a modest finite number (a probability above 2^16, inf, NaN) means the
-    // reference is too low for this half
+    // reference is too low for this window
     auto overflowed = [&](float sum) { return __builtin_amdgcn_ballot_w64(!(sum <= 65536.0f)) != 0; };
-    auto mask_half = [&](int half, int limit) {
+    bool first_block = true;
+    auto check_window = [&](int c) {                   // at slot boundary kCheckSlot[c]
+        const int q_lo = c == 0 ? 0 : pairs_by(kCheckSlot[c - 1] - 1), q_hi = pairs_by(kCheckSlot[c] - 1);
+        if ((c == 0 && first_block) || overflowed(window_sum())) fix_window(q_lo, q_hi);
+        l_run += window_sum();
+        clear_sum();
+    };
+    // accumulator x of tile t is key t*32 + 16*(x/8) + 8*hi + x%8 of the block
+    auto mask_tile = [&](int t, int limit) {
 #pragma unroll
-        for (int t = half * HT; t < (half + 1) * HT; ++t)
-#pragma unroll
-            for (int x = 0; x < 16; ++x)
-                if (t * 32 + 16 * (x >> 3) + (x & 7) > limit) s_acc[t][x] = neg_inf;
+        for (int x = 0; x < 16; ++x)
+            if (t * 32 + 16 * (x >> 3) + (x & 7) > limit) s_acc[t][x] = neg_inf;
     };
 
-    bool first_block = true;
+    constexpr int kStepsPerRequestV = (NS / 2) / 8;    // V's 8 requests go under the first half of S^T,
+    constexpr int kStepsPerRequestK = NS / 8;          // the next K's under all of O^T
+    const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
     for (int it = 0; it < cnt; ++it) {
         const int j = clamped(j_cur);
         const bool has_next = it + 1 < cnt;
-        const int j_nxt = has_next ? list[it + 1] : 0;  // scalar load, consumed after S^T
-        // accumulator x of tile t is key t*32 + 16*(x/8) + 8*hi + x%8 of the block: on the diagonal
-        // block keys above the query are masked; an unusable entry is masked entirely
+        if (((it + 1) & 63) == 0) list_reg = list_chunk(it + 1);
+        // on the diagonal block keys above the query are masked; an unusable entry is masked entirely
         const bool masked = (j == i) || !usable(j_cur);
         const int mask_limit = usable(j_cur) ? qrow - 8 * hi + (i - j) : -1;
 
+        // the bases are made opaque once per block so that the swizzled offsets are recomputed
+        // next to their reads instead of being kept in a dozen registers across the loop
+        asm volatile("" : "+v"(k_base), "+v"(v_base));
         STEM_WAIT_VMCNT(0);
         STEM_BARRIER();                                // K(j) is in LDS; V buffer is free
-        const auto v_rq = v_request(j);
 
-        // ---- S^T, first half, with the V requests in between ----
-        uint4 ka[2][4];
-        load_k_group(0, ka[0]);
+        // ---- S^T = K Q^T, with the V requests in between during the first half ----
+        uint4 ka[kSlots];
+#pragma unroll
+        for (int n = 0; n < kAhead; ++n) ka[n] = load_k(n);
+        const auto v_rq = v_request(j);
+        const int j_nxt = __builtin_amdgcn_readlane(list_reg, (it + 1) & 63);   // 0 past the end
+        off = m_ref * sl2;                             // -inf on the first block: redone at the first check
+        clear_sum();
         STEM_SCHED_FENCE();
 #pragma unroll
-        for (int grp = 0; grp < HG; ++grp) {
-            load_k_group(grp + 1, ka[(grp + 1) & 1]);
+        for (int t = 0; t < KT; ++t) {
 #pragma unroll
-            for (int x = 0; x < 8 / HG; ++x) v_rq.issue(grp * (8 / HG) + x, v_slice0);
-            STEM_SCHED_FENCE();
-            const int t = grp >> 1, part = grp & 1;
-            if (part == 0) {
-#pragma unroll
-                for (int x = 0; x < 16; ++x) s_acc[t][x] = 0.f;
-            }
-#pragma unroll
-            for (int x = 0; x < 4; ++x)
-                s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[grp & 1][x]), q_reg[part * 4 + x],
-                                                                  s_acc[t], 0, 0, 0);
-            STEM_SCHED_FENCE();
-        }
-        if (masked) mask_half(0, mask_limit);
-
-        // ---- S^T, second half, one matrix instruction per step, with the first half's softmax
-        //      (one accumulator pair per step) issued in its shadow ----
-        {
-            const float off = m_ref * sl2;             // -inf on the first block: redone below
-#pragma unroll
-            for (int e = 0; e < 4; ++e) ps[0][e] = 0.f;
-#pragma unroll
-            for (int grp = HG; grp < 2 * HG; ++grp) {
-                if (grp + 1 < 2 * HG) load_k_group(grp + 1, ka[(grp + 1) & 1]);
+            for (int n = t * 8; n < t * 8 + 8; ++n) {
+                if ((n & 1) == 0) {
+                    if (n + kAhead < NS) ka[(n + kAhead) % kSlots] = load_k(n + kAhead);
+                    if (n + kAhead + 1 < NS) ka[(n + kAhead + 1) % kSlots] = load_k(n + kAhead + 1);
+                    wait_lgkmcnt((n + kAhead + 2 < NS ? kAhead + 2 : NS - n) - 2);
+                }
+                if (n < NS / 2 && n % kStepsPerRequestV == 0)
+                    v_rq.issue(n / kStepsPerRequestV, v_slice0, slice_step, slice_lds_step);
+                s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[n % kSlots]), q_reg[n & 7],
+                                                                  (n & 7) == 0 ? zero16 : s_acc[t], 0, 0, 0);
+                softmax_slot(n);
                 STEM_SCHED_FENCE();
-                const int t = grp >> 1, part = grp & 1;
-                if (part == 0) {
-#pragma unroll
-                    for (int x = 0; x < 16; ++x) s_acc[t][x] = 0.f;
-                }
-#pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[grp & 1][x]), q_reg[part * 4 + x],
-                                                                      s_acc[t], 0, 0, 0);
-                    const int n = (grp - HG) * 4 + x;  // softmax step: pair n of the first half
-                    softmax_pair(0, n >> 3, (n & 7) * 2, off);
-                    STEM_SCHED_FENCE();
-                }
             }
+            if (masked) mask_tile(t, mask_limit);
         }
-        STEM_BARRIER();                                // every wave is done with K(j)
-        const auto k_rq = k_request(clamped(j_nxt));   // issued inside the first part of O^T (if has_next)
-        if (masked) mask_half(1, mask_limit);
-        if (first_block || overflowed(half_sum(0))) fix_half(0);
-        first_block = false;
-        l_run += half_sum(0);
 
         STEM_WAIT_VMCNT(0);
-        STEM_BARRIER();                                // V(j) is in LDS
+        STEM_BARRIER();                                // every wave is done with K(j); V(j) is in LDS
 
-        // ---- O^T, first half of the keys, with the second half's softmax in its shadow and the
-        //      next block's K requests in between ----
-        uint4 va[2][4];
-        load_v_step(0, va[0]);
+        // ---- O^T += V^T P^T.  The next block's K requests are spread over the whole product;
+        //      after the last block they are empty (a zero-sized resource: nothing is fetched) ----
+        uint4 va[kSlots];
+#pragma unroll
+        for (int n = 0; n < kAhead; ++n) va[n] = load_v(n);
+        const auto k_rq = k_request(clamped(j_nxt), has_next);
         STEM_SCHED_FENCE();
-        {
-            const float off = m_ref * sl2;
+        auto pv_range = [&](int n_lo, int n_hi) {      // even bounds
 #pragma unroll
-            for (int e = 0; e < 4; ++e) ps[1][e] = 0.f;
-#pragma unroll
-            for (int g2 = 0; g2 < HG; ++g2) {
-                load_v_step(g2 + 1, va[(g2 + 1) & 1]);
-                if (has_next) {
-#pragma unroll
-                    for (int x = 0; x < 8 / HG; ++x) k_rq.issue(g2 * (8 / HG) + x, k_slice0);
+            for (int n = n_lo; n < n_hi; ++n) {
+                if ((n & 1) == 0) {
+                    if (n + kAhead < NS) va[(n + kAhead) % kSlots] = load_v(n + kAhead);
+                    wait_lgkmcnt(2 * ((n + kAhead + 1 < NS ? kAhead + 1 : NS - n) - 2));
+                } else {
+                    if (n + kAhead < NS) va[(n + kAhead) % kSlots] = load_v(n + kAhead);
                 }
-                STEM_SCHED_FENCE();
-                const int t = g2 >> 1, u = g2 & 1;
+                if (n % kStepsPerRequestK == 1) k_rq.issue(n / kStepsPerRequestK, k_slice0, slice_step, slice_lds_step);
+                const int g2 = n >> 2, t = g2 >> 1, u = g2 & 1, dt = n & 3;
                 const uint4 pb = make_uint4(p_pk[t][u * 4], p_pk[t][u * 4 + 1], p_pk[t][u * 4 + 2], p_pk[t][u * 4 + 3]);
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[g2 & 1][dt]), as_bf16x8(pb),
-                                                                       o_acc[dt], 0, 0, 0);
-                    const int n = g2 * 4 + dt;         // softmax step: pair n of the second half
-                    softmax_pair(1, HT + (n >> 3), (n & 7) * 2, off);
-                    STEM_SCHED_FENCE();
-                }
-            }
-        }
-        if (overflowed(half_sum(1))) fix_half(1);
-        l_run += half_sum(1);
-
-        // ---- O^T, second half of the keys ----
-#pragma unroll
-        for (int g2 = HG; g2 < 2 * HG; ++g2) {
-            if (g2 + 1 < 2 * HG) load_v_step(g2 + 1, va[(g2 + 1) & 1]);
-            STEM_SCHED_FENCE();
-            const int t = g2 >> 1, u = g2 & 1;
-            const uint4 pb = make_uint4(p_pk[t][u * 4], p_pk[t][u * 4 + 1], p_pk[t][u * 4 + 2], p_pk[t][u * 4 + 3]);
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-                o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[g2 & 1][dt]), as_bf16x8(pb),
+                o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[n % kSlots]), as_bf16x8(pb),
                                                                    o_acc[dt], 0, 0, 0);
-            STEM_SCHED_FENCE();
+                softmax_slot(NS + n);
+                STEM_SCHED_FENCE();
+            }
+        };
+        check_window(0);
+        first_block = false;
+        pv_range(0, kCheckSlot[1] - NS);
+        check_window(1);
+        if (kChecks == 3) {
+            pv_range(kCheckSlot[1] - NS, kCheckSlot[2] - NS);
+            check_window(2);
+            pv_range(kCheckSlot[2] - NS, NS);
+        } else {
+            pv_range(kCheckSlot[1] - NS, NS);
         }
         j_cur = j_nxt;
     }
+    STEM_WAIT_VMCNT(0);                                // no request may outlive the workgroup's LDS
 
     // ---- normalise and store: accumulator x of d tile dt is column dt*32 + 8*(x/4) + 4*hi + x%4 ----
     float l_tot;
@@ -448,6 +462,12 @@ __global__ __launch_bounds__(B * 2, 2) void sparse_attn_kernel(
 int launch_sparse_attn(const Problem& p, const void* q, const void* k, const void* v,
                        const int32_t* counts, const int32_t* indices, int32_t kmax,
                        float softmax_scale, void* out, float* lse, hipStream_t stream) {
+    // the block requests address one sequence of one KV head through a 32-bit byte offset, with
+    // offsets from 2^31 on reserved for requests that must fetch nothing
+    for (int s = 0; s < p.batch; ++s) {
+        const int64_t rows = p.seq.tok_start[s + 1] - p.seq.tok_start[s];
+        if (rows > 0 && (rows - 1) * p.kv_st * 2 + kHeadDim * 2 > 0x7fffffffll) return STEM_ERR_UNSUPPORTED;
+    }
     const int64_t items = (int64_t)p.Hq * p.R;
     const int64_t per_xcd = (items + 7) / 8;
     if (per_xcd * 8 > 0x7fffffff) return STEM_ERR_UNSUPPORTED;
