@@ -70,12 +70,25 @@ const char* stem_strerror(int status);
 /* R (total query-block rows) and NBmax (blocks of the longest sequence) of a shape. */
 int stem_rows(const stem_shape* shape, int32_t* host_total_rows, int32_t* host_max_blocks);
 
-/* Bytes of device workspace stem_estimate / stem_pool need for this shape.  Layout (fp32):
- *   q_bar [Hq, R, d] | k_bar [Hkv, R, d] | m_v [Hkv, R]   (each part starts 256-byte aligned). */
-int stem_workspace_bytes(const stem_shape* shape, size_t* host_bytes);
+/*
+ * ad_stride S, taken by the stage-1 entry points: the stride of the anti-diagonal sample that the
+ * pooled routing term stands for (Algorithm 1 steps 1 and 3a).  A block keeps S partial means,
+ * one per residue class of the in-block token position modulo S, and the routing term of a block
+ * pair is the mean over the positions (r, c) with (r + c) mod S = S - 1 of <Q_r, K_c>:
+ *     route = (1 / S) * sum over a < S of <q_bar[.., a, :], k_bar[.., S - 1 - a, :]>.
+ * S = 1 is block-mean pooling (one vector per block, the 2 N^2 d / B^2 metric cost of the
+ * Complexity Analysis); larger S samples the block's logits more finely at S times the cost.
+ * Supported: S in {1, 2, 4, 8, 16}; other divisors of B return STEM_ERR_UNSUPPORTED, values that
+ * do not divide B or are < 1 STEM_ERR_INVALID_ARG.
+ */
+
+/* Bytes of device workspace stem_estimate / stem_pool need for this shape and ad_stride S.
+ * Layout (fp32):
+ *   q_bar [Hq, R, S, d] | k_bar [Hkv, R, S, d] | m_v [Hkv, R]   (each part 256-byte aligned). */
+int stem_workspace_bytes(const stem_shape* shape, int32_t ad_stride, size_t* host_bytes);
 
 /* Byte offsets of the three workspace parts (for callers that want to look at them). */
-int stem_workspace_layout(const stem_shape* shape, size_t* host_q_bar_offset,
+int stem_workspace_layout(const stem_shape* shape, int32_t ad_stride, size_t* host_q_bar_offset,
                           size_t* host_k_bar_offset, size_t* host_m_v_offset);
 
 /*
@@ -93,24 +106,26 @@ int stem_budget_schedule(const stem_shape* shape, const double* host_k_start_blo
 
 /*
  * Algorithm 1 step 1: pooled block representations into the workspace (layout above).
- *   q_bar[h, r, :] = mean over the valid tokens of row r's block of Q[t, h, :]      (fp32)
- *   k_bar[g, r, :] = the same for K
- *   m_v[g, r]      = max over the block's valid tokens of ln ||V[t, g, :]||_2  (-inf if all zero)
+ *   q_bar[h, r, a, :] = mean of Q[t, h, :] over the valid tokens t of row r's block whose in-block
+ *                       position is congruent to a modulo S (zeros if there is none)     (fp32)
+ *   k_bar[g, r, a, :] = the same for K
+ *   m_v[g, r]         = max over the block's valid tokens of ln ||V[t, g, :]||_2  (-inf if all zero)
  */
 int stem_pool(const stem_shape* shape, const void* q, const void* k, const void* v,
-              void* workspace, size_t workspace_bytes, void* hip_stream);
+              int32_t ad_stride, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
- * Algorithm 1 step 3a, Eq. 7, from a pooled workspace:
- *   scores[h, r, j] = route_scale * <q_bar[h, r], k_bar[g, row0(r) + j]> + beta * max(0, m_v[g, row0(r) + j])
- * for 0 <= j <= i(r); -inf for i(r) < j < NBmax.  scores is fp32 [Hq, R, NBmax].
+ * Algorithm 1 step 3a, Eq. 7, from a workspace pooled with the same ad_stride:
+ *   scores[h, r, j] = route_scale * route(h, r, j) + beta * max(0, m_v[g, row0(r) + j])
+ * for 0 <= j <= i(r); -inf for i(r) < j < NBmax, with route as defined above from q_bar[h, r] and
+ * k_bar[g, row0(r) + j].  scores is fp32 [Hq, R, NBmax].
  * route_scale = 1 is Eq. 7 as printed; 1/sqrt(d) gives the scaling of Eq. 6.
  */
 int stem_block_scores(const stem_shape* shape, const void* workspace, size_t workspace_bytes,
-                      float beta, float route_scale, float* scores, void* hip_stream);
+                      int32_t ad_stride, float beta, float route_scale, float* scores,
+                      void* hip_stream);
 
-/* Stage 1 = stem_pool followed by stem_block_scores.  ad_stride must be 1 (block-mean pooling);
- * other anti-diagonal strides return STEM_ERR_UNSUPPORTED. */
+/* Stage 1 = stem_pool followed by stem_block_scores with the same ad_stride. */
 int stem_estimate(const stem_shape* shape, const void* q, const void* k, const void* v,
                   float beta, float route_scale, int32_t ad_stride, float* scores,
                   void* workspace, size_t workspace_bytes, void* hip_stream);

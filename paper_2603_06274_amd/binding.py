@@ -59,12 +59,12 @@ def lib() -> ctypes.CDLL:
         L.stem_strerror.argtypes = [ctypes.c_int]
         sigs = {
             "stem_rows": [shp, ctypes.POINTER(i32), ctypes.POINTER(i32)],
-            "stem_workspace_bytes": [shp, ctypes.POINTER(sz)],
-            "stem_workspace_layout": [shp, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(sz)],
+            "stem_workspace_bytes": [shp, i32, ctypes.POINTER(sz)],
+            "stem_workspace_layout": [shp, i32, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(sz)],
             "stem_budget_schedule": [shp, ctypes.POINTER(ctypes.c_double), ctypes.c_double, i32, i32, i32,
                                      ctypes.POINTER(i32), ctypes.POINTER(i32)],
-            "stem_pool": [shp, vp, vp, vp, vp, sz, vp],
-            "stem_block_scores": [shp, vp, sz, f32, f32, vp, vp],
+            "stem_pool": [shp, vp, vp, vp, i32, vp, sz, vp],
+            "stem_block_scores": [shp, vp, sz, i32, f32, f32, vp, vp],
             "stem_estimate": [shp, vp, vp, vp, f32, f32, i32, vp, vp, sz, vp],
             "stem_select": [shp, vp, vp, i32, i32, vp, vp, i32, vp],
             "stem_sparse_attn": [shp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp],
@@ -131,16 +131,16 @@ def stem_rows(shape: Shape) -> Tuple[int, int]:
     return r.value, nb.value
 
 
-def stem_workspace_bytes(shape: Shape) -> int:
+def stem_workspace_bytes(shape: Shape, ad_stride: int = 1) -> int:
     n = ctypes.c_size_t()
-    _check(lib().stem_workspace_bytes(shape.ref(), ctypes.byref(n)), "stem_workspace_bytes")
+    _check(lib().stem_workspace_bytes(shape.ref(), int(ad_stride), ctypes.byref(n)), "stem_workspace_bytes")
     return n.value
 
 
-def stem_workspace_layout(shape: Shape) -> Tuple[int, int, int]:
+def stem_workspace_layout(shape: Shape, ad_stride: int = 1) -> Tuple[int, int, int]:
     a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
-    _check(lib().stem_workspace_layout(shape.ref(), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)),
-           "stem_workspace_layout")
+    _check(lib().stem_workspace_layout(shape.ref(), int(ad_stride), ctypes.byref(a), ctypes.byref(b),
+                                       ctypes.byref(c)), "stem_workspace_layout")
     return a.value, b.value, c.value
 
 
@@ -157,16 +157,17 @@ def stem_budget_schedule(shape: Shape, k_start_blocks: Sequence[float], mu: floa
     return out[:rows], kmax.value
 
 
-def stem_pool(shape: Shape, q, k, v, workspace: torch.Tensor) -> None:
-    _check(lib().stem_pool(shape.ref(), _ptr(q), _ptr(k), _ptr(v), _ptr(workspace),
+def stem_pool(shape: Shape, q, k, v, ad_stride: int, workspace: torch.Tensor) -> None:
+    _check(lib().stem_pool(shape.ref(), _ptr(q), _ptr(k), _ptr(v), int(ad_stride), _ptr(workspace),
                            workspace.numel() * workspace.element_size(), _stream()), "stem_pool")
 
 
-def stem_block_scores(shape: Shape, workspace: torch.Tensor, beta: float, route_scale: float,
-                      scores: torch.Tensor) -> None:
+def stem_block_scores(shape: Shape, workspace: torch.Tensor, ad_stride: int, beta: float,
+                      route_scale: float, scores: torch.Tensor) -> None:
     _check(lib().stem_block_scores(shape.ref(), _ptr(workspace),
-                                   workspace.numel() * workspace.element_size(), float(beta),
-                                   float(route_scale), _ptr(scores), _stream()), "stem_block_scores")
+                                   workspace.numel() * workspace.element_size(), int(ad_stride),
+                                   float(beta), float(route_scale), _ptr(scores), _stream()),
+           "stem_block_scores")
 
 
 def stem_estimate(shape: Shape, q, k, v, beta: float, route_scale: float, ad_stride: int,

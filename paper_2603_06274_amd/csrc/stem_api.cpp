@@ -62,11 +62,17 @@ int make_problem(const stem_shape* s, Problem* out) {
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-WorkspaceLayout workspace_layout(const Problem& p) {
+int check_ad_stride(const Problem& p, int ad_stride) {
+    if (ad_stride < 1 || p.B % ad_stride) return STEM_ERR_INVALID_ARG;
+    if (ad_stride > 16) return STEM_ERR_UNSUPPORTED;   // divisors of 64 / 128 up to 16 are 1, 2, 4, 8, 16
+    return STEM_OK;
+}
+
+WorkspaceLayout workspace_layout(const Problem& p, int ad_stride) {
     WorkspaceLayout w;
     w.q_bar = 0;
-    w.k_bar = align256(w.q_bar + sizeof(float) * (size_t)p.Hq * p.R * kHeadDim);
-    w.m_v = align256(w.k_bar + sizeof(float) * (size_t)p.Hkv * p.R * kHeadDim);
+    w.k_bar = align256(w.q_bar + sizeof(float) * (size_t)p.Hq * p.R * ad_stride * kHeadDim);
+    w.m_v = align256(w.k_bar + sizeof(float) * (size_t)p.Hkv * p.R * ad_stride * kHeadDim);
     w.total = align256(w.m_v + sizeof(float) * (size_t)p.Hkv * p.R);
     if (w.total == 0) w.total = 256;
     return w;
@@ -78,7 +84,7 @@ using namespace stem;
 
 extern "C" {
 
-int stem_version(void) { return 100; }
+int stem_version(void) { return 200; }
 
 const char* stem_strerror(int status) {
     switch (status) {
@@ -100,21 +106,23 @@ int stem_rows(const stem_shape* shape, int32_t* host_total_rows, int32_t* host_m
     return STEM_OK;
 }
 
-int stem_workspace_bytes(const stem_shape* shape, size_t* host_bytes) {
+int stem_workspace_bytes(const stem_shape* shape, int32_t ad_stride, size_t* host_bytes) {
     Problem p;
     int st = make_problem(shape, &p);
     if (st != STEM_OK) return st;
+    if ((st = check_ad_stride(p, ad_stride)) != STEM_OK) return st;
     if (!host_bytes) return STEM_ERR_INVALID_ARG;
-    *host_bytes = workspace_layout(p).total;
+    *host_bytes = workspace_layout(p, ad_stride).total;
     return STEM_OK;
 }
 
-int stem_workspace_layout(const stem_shape* shape, size_t* host_q_bar_offset,
+int stem_workspace_layout(const stem_shape* shape, int32_t ad_stride, size_t* host_q_bar_offset,
                           size_t* host_k_bar_offset, size_t* host_m_v_offset) {
     Problem p;
     int st = make_problem(shape, &p);
     if (st != STEM_OK) return st;
-    WorkspaceLayout w = workspace_layout(p);
+    if ((st = check_ad_stride(p, ad_stride)) != STEM_OK) return st;
+    WorkspaceLayout w = workspace_layout(p, ad_stride);
     if (host_q_bar_offset) *host_q_bar_offset = w.q_bar;
     if (host_k_bar_offset) *host_k_bar_offset = w.k_bar;
     if (host_m_v_offset) *host_m_v_offset = w.m_v;
@@ -161,34 +169,37 @@ static int check_qkv(const void* q, const void* k, const void* v) {
     return STEM_OK;
 }
 
-int stem_pool(const stem_shape* shape, const void* q, const void* k, const void* v, void* workspace,
-              size_t workspace_bytes, void* hip_stream) {
+int stem_pool(const stem_shape* shape, const void* q, const void* k, const void* v, int32_t ad_stride,
+              void* workspace, size_t workspace_bytes, void* hip_stream) {
     Problem p;
     int st = make_problem(shape, &p);
     if (st != STEM_OK) return st;
+    if ((st = check_ad_stride(p, ad_stride)) != STEM_OK) return st;
     if ((st = check_qkv(q, k, v)) != STEM_OK) return st;
     if (!workspace || !aligned16(workspace)) return STEM_ERR_INVALID_ARG;
-    WorkspaceLayout w = workspace_layout(p);
+    WorkspaceLayout w = workspace_layout(p, ad_stride);
     if (workspace_bytes < w.total) return STEM_ERR_WORKSPACE;
     if (p.R == 0) return STEM_OK;
     char* ws = static_cast<char*>(workspace);
-    return launch_pool(p, q, k, v, reinterpret_cast<float*>(ws + w.q_bar),
+    return launch_pool(p, ad_stride, q, k, v, reinterpret_cast<float*>(ws + w.q_bar),
                        reinterpret_cast<float*>(ws + w.k_bar), reinterpret_cast<float*>(ws + w.m_v),
                        static_cast<hipStream_t>(hip_stream));
 }
 
 int stem_block_scores(const stem_shape* shape, const void* workspace, size_t workspace_bytes,
-                      float beta, float route_scale, float* scores, void* hip_stream) {
+                      int32_t ad_stride, float beta, float route_scale, float* scores,
+                      void* hip_stream) {
     Problem p;
     int st = make_problem(shape, &p);
     if (st != STEM_OK) return st;
+    if ((st = check_ad_stride(p, ad_stride)) != STEM_OK) return st;
     if (!workspace || !aligned16(workspace) || !scores || !aligned16(scores)) return STEM_ERR_INVALID_ARG;
     if (!std::isfinite(beta) || !std::isfinite(route_scale)) return STEM_ERR_INVALID_ARG;
-    WorkspaceLayout w = workspace_layout(p);
+    WorkspaceLayout w = workspace_layout(p, ad_stride);
     if (workspace_bytes < w.total) return STEM_ERR_WORKSPACE;
     if (p.R == 0) return STEM_OK;
     const char* ws = static_cast<const char*>(workspace);
-    return launch_block_scores(p, reinterpret_cast<const float*>(ws + w.q_bar),
+    return launch_block_scores(p, ad_stride, reinterpret_cast<const float*>(ws + w.q_bar),
                                reinterpret_cast<const float*>(ws + w.k_bar),
                                reinterpret_cast<const float*>(ws + w.m_v), beta, route_scale, scores,
                                static_cast<hipStream_t>(hip_stream));
@@ -197,16 +208,16 @@ int stem_block_scores(const stem_shape* shape, const void* workspace, size_t wor
 int stem_estimate(const stem_shape* shape, const void* q, const void* k, const void* v, float beta,
                   float route_scale, int32_t ad_stride, float* scores, void* workspace,
                   size_t workspace_bytes, void* hip_stream) {
-    if (ad_stride < 1) return STEM_ERR_INVALID_ARG;
     if (!scores || !aligned16(scores)) return STEM_ERR_INVALID_ARG;
     if (!std::isfinite(beta) || !std::isfinite(route_scale)) return STEM_ERR_INVALID_ARG;
     Problem p;
     int st = make_problem(shape, &p);
     if (st != STEM_OK) return st;
-    if (ad_stride != 1) return STEM_ERR_UNSUPPORTED;
-    st = stem_pool(shape, q, k, v, workspace, workspace_bytes, hip_stream);
+    if ((st = check_ad_stride(p, ad_stride)) != STEM_OK) return st;
+    st = stem_pool(shape, q, k, v, ad_stride, workspace, workspace_bytes, hip_stream);
     if (st != STEM_OK) return st;
-    return stem_block_scores(shape, workspace, workspace_bytes, beta, route_scale, scores, hip_stream);
+    return stem_block_scores(shape, workspace, workspace_bytes, ad_stride, beta, route_scale, scores,
+                             hip_stream);
 }
 
 int stem_select(const stem_shape* shape, const float* scores, const int32_t* budget, int32_t n_sink,

@@ -30,13 +30,16 @@ int make_problem(const stem_shape* shape, Problem* out);
 struct WorkspaceLayout {
     size_t q_bar, k_bar, m_v, total;
 };
-WorkspaceLayout workspace_layout(const Problem& p);
+WorkspaceLayout workspace_layout(const Problem& p, int ad_stride);
+// STEM_OK if S is a supported anti-diagonal stride for this block size.
+int check_ad_stride(const Problem& p, int ad_stride);
 
 // Kernel launchers (one per translation unit); each returns a STEM_* status.
-int launch_pool(const Problem& p, const void* q, const void* k, const void* v, float* q_bar,
-                float* k_bar, float* m_v, hipStream_t stream);
-int launch_block_scores(const Problem& p, const float* q_bar, const float* k_bar, const float* m_v,
-                        float beta, float route_scale, float* scores, hipStream_t stream);
+int launch_pool(const Problem& p, int ad_stride, const void* q, const void* k, const void* v,
+                float* q_bar, float* k_bar, float* m_v, hipStream_t stream);
+int launch_block_scores(const Problem& p, int ad_stride, const float* q_bar, const float* k_bar,
+                        const float* m_v, float beta, float route_scale, float* scores,
+                        hipStream_t stream);
 int launch_select(const Problem& p, const float* scores, const int32_t* budget, int32_t n_sink,
                   int32_t n_local, int32_t* counts, int32_t* indices, int32_t kmax,
                   hipStream_t stream);

@@ -5,6 +5,11 @@
 // 256 threads = 16 token lanes x 16 column chunks; every thread issues all of its loads (B/16
 // tokens) before it touches the first value, so a workgroup keeps B x 256 B in flight.  Column
 // sums are reduced across the 16 token lanes through LDS in a fixed order (deterministic fp32).
+//
+// With an anti-diagonal stride S > 1 (S divides 16) a block keeps S partial means, one per residue
+// class of the in-block token position modulo S.  A thread's tokens tl, tl + 16, ... all fall in
+// class tl mod S, so the only change is that the LDS reduction adds the 16 / S token lanes of each
+// class separately.
 #include "stem_common.h"
 
 namespace stem {
@@ -15,7 +20,7 @@ template <int B>
 __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     float* __restrict__ q_bar, float* __restrict__ k_bar, float* __restrict__ m_v, SeqTable seq,
-    int Hq, int Hkv, int R, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh) {
+    int Hq, int Hkv, int R, int S, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh) {
     constexpr int kTok = B / 16;                       // tokens per thread
     const int slots = Hq + 2 * Hkv;
     const int r = blockIdx.x / slots;
@@ -63,12 +68,13 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) part[tl][c * 8 + e] = acc[e];
         __syncthreads();
-        if (tid < kHeadDim) {
+        float* dst = (kind == 0 ? q_bar : k_bar) + ((int64_t)head * R + r) * S * kHeadDim;
+        for (int o = tid; o < S * kHeadDim; o += kPoolThreads) {
+            const int a = o >> 7, col = o & (kHeadDim - 1);   // residue class, column
             float sum = 0.f;
-#pragma unroll
-            for (int x = 0; x < 16; ++x) sum += part[x][tid];
-            float* dst = (kind == 0 ? q_bar : k_bar) + ((int64_t)head * R + r) * kHeadDim;
-            dst[tid] = sum / (float)n_valid;
+            for (int x = a; x < 16; x += S) sum += part[x][col];
+            const int members = (n_valid - a + S - 1) / S;    // valid tokens of the class (n_valid > a)
+            dst[o] = n_valid > a ? sum / (float)members : 0.f;
         }
     } else {
         // squared L2 norm of each token row: 8 columns per lane, then across the 16 chunk lanes
@@ -98,8 +104,9 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
     }
 }
 
-int launch_pool(const Problem& p, const void* q, const void* k, const void* v, float* q_bar,
-                float* k_bar, float* m_v, hipStream_t stream) {
+int launch_pool(const Problem& p, int ad_stride, const void* q, const void* k, const void* v,
+                float* q_bar, float* k_bar, float* m_v, hipStream_t stream) {
+    if (ad_stride < 1 || 16 % ad_stride) return STEM_ERR_UNSUPPORTED;
     const int64_t blocks = (int64_t)p.R * (p.Hq + 2 * p.Hkv);
     if (blocks > 0x7fffffff) return STEM_ERR_UNSUPPORTED;
     dim3 grid((unsigned)blocks), block(kPoolThreads);
@@ -108,10 +115,10 @@ int launch_pool(const Problem& p, const void* q, const void* k, const void* v, f
     const uint16_t* vv = static_cast<const uint16_t*>(v);
     if (p.B == 128)
         hipLaunchKernelGGL(pool_kernel<128>, grid, block, 0, stream, qq, kk, vv, q_bar, k_bar, m_v,
-                           p.seq, p.Hq, p.Hkv, p.R, p.q_st, p.q_sh, p.kv_st, p.kv_sh);
+                           p.seq, p.Hq, p.Hkv, p.R, ad_stride, p.q_st, p.q_sh, p.kv_st, p.kv_sh);
     else
         hipLaunchKernelGGL(pool_kernel<64>, grid, block, 0, stream, qq, kk, vv, q_bar, k_bar, m_v,
-                           p.seq, p.Hq, p.Hkv, p.R, p.q_st, p.q_sh, p.kv_st, p.kv_sh);
+                           p.seq, p.Hq, p.Hkv, p.R, ad_stride, p.q_st, p.q_sh, p.kv_st, p.kv_sh);
     return check_launch();
 }
 

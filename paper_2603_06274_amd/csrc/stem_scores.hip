@@ -1,7 +1,9 @@
 // Stage 1b (Algorithm 1 step 3a, Eq. 7): coarse Output-Aware Metric of every causal block pair,
-//   scores[h, r, j] = route_scale * <q_bar[h, r], k_bar[g, row0 + j]> + beta * max(0, m_v[g, row0 + j]).
+//   scores[h, r, j] = route_scale * route(h, r, j) + beta * max(0, m_v[g, row0 + j]),
+//   route = (1 / S) * sum over residue classes a < S of <q_bar[h, r, a], k_bar[g, row0 + j, S - 1 - a]>
+// (S = 1: the plain product of the two block means).
 //
-// A small fp32 contraction over d = 128 per head and sequence, lower-triangular in (i, j).  It is
+// A small fp32 contraction over S * d per head and sequence, lower-triangular in (i, j).  It is
 // kept in full fp32 FMA arithmetic (no bf16 matrix cores) because stage 2 ranks these numbers and
 // must reproduce the ranking of an fp64 evaluation except for genuine near-ties.  64 x 64 output
 // tiles, 4 x 4 per thread, operands staged k-major through LDS; tiles above the diagonal are only
@@ -20,8 +22,8 @@ struct TileTable {
 
 __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
     const float* __restrict__ q_bar, const float* __restrict__ k_bar, const float* __restrict__ m_v,
-    float* __restrict__ scores, SeqTable seq, TileTable tiles, int R, int NBmax, int G, float beta,
-    float route_scale) {
+    float* __restrict__ scores, SeqTable seq, TileTable tiles, int R, int NBmax, int G, int S,
+    float beta, float route_scale) {
     // sequence and local row tile of this workgroup
     int s = 0;
     for (int x = 1; x < seq.batch; ++x) s = ((int)blockIdx.x >= tiles.tile_start[x]) ? x : s;
@@ -60,18 +62,21 @@ __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
 #pragma unroll
         for (int y = 0; y < 4; ++y) acc[x][y] = 0.f;
 
-    const float* a_src = q_bar + ((int64_t)h * R + row0) * kHeadDim;
-    const float* b_src = k_bar + ((int64_t)g * R + row0) * kHeadDim;
+    const int depth = S * kHeadDim;                    // floats per pooled block
+    const float* a_src = q_bar + ((int64_t)h * R + row0) * depth;
+    const float* b_src = k_bar + ((int64_t)g * R + row0) * depth;
 
-    for (int kc = 0; kc < kHeadDim; kc += kChunk) {
+    for (int kc = 0; kc < depth; kc += kChunk) {
+        // a chunk lies inside one residue class a of the query block; its partner is class S-1-a
+        const int kb = (S - 1 - (kc >> 7)) * kHeadDim + (kc & (kHeadDim - 1));
         // 64 rows x 32 floats per operand = 512 float4; two per thread and operand
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int idx = tid + kScoreThreads * u;
             const int row = idx >> 3, c4 = (idx & 7) * 4;
             float4 av = make_float4(0.f, 0.f, 0.f, 0.f), bv = av;
-            if (i0 + row < n) av = *reinterpret_cast<const float4*>(a_src + (int64_t)(i0 + row) * kHeadDim + kc + c4);
-            if (j0 + row < n) bv = *reinterpret_cast<const float4*>(b_src + (int64_t)(j0 + row) * kHeadDim + kc + c4);
+            if (i0 + row < n) av = *reinterpret_cast<const float4*>(a_src + (int64_t)(i0 + row) * depth + kc + c4);
+            if (j0 + row < n) bv = *reinterpret_cast<const float4*>(b_src + (int64_t)(j0 + row) * depth + kb + c4);
             a_s[c4 + 0][row] = av.x; a_s[c4 + 1][row] = av.y; a_s[c4 + 2][row] = av.z; a_s[c4 + 3][row] = av.w;
             b_s[c4 + 0][row] = bv.x; b_s[c4 + 1][row] = bv.y; b_s[c4 + 2][row] = bv.z; b_s[c4 + 3][row] = bv.w;
         }
@@ -104,13 +109,14 @@ __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
         for (int y = 0; y < 4; ++y) {
             const int j = j0 + tj * 4 + y;
             if (j >= NBmax) continue;
-            out[(int64_t)i * NBmax + j] = (j <= i) ? fmaf(route_scale, acc[x][y], mag[y]) : neg_inf;
+            out[(int64_t)i * NBmax + j] = (j <= i) ? fmaf(route_scale / (float)S, acc[x][y], mag[y]) : neg_inf;
         }
     }
 }
 
-int launch_block_scores(const Problem& p, const float* q_bar, const float* k_bar, const float* m_v,
-                        float beta, float route_scale, float* scores, hipStream_t stream) {
+int launch_block_scores(const Problem& p, int ad_stride, const float* q_bar, const float* k_bar,
+                        const float* m_v, float beta, float route_scale, float* scores,
+                        hipStream_t stream) {
     TileTable tiles;
     int total = 0;
     for (int s = 0; s <= STEM_MAX_BATCH; ++s) {
@@ -121,7 +127,7 @@ int launch_block_scores(const Problem& p, const float* q_bar, const float* k_bar
     if (p.Hq > 65535) return STEM_ERR_UNSUPPORTED;
     dim3 grid(total, (p.NBmax + kTile - 1) / kTile, p.Hq), block(kScoreThreads);
     hipLaunchKernelGGL(block_scores_kernel, grid, block, 0, stream, q_bar, k_bar, m_v, scores, p.seq,
-                       tiles, p.R, p.NBmax, p.G, beta, route_scale);
+                       tiles, p.R, p.NBmax, p.G, ad_stride, beta, route_scale);
     return check_launch();
 }
 

@@ -18,7 +18,7 @@ class StemPrefill:
     def __init__(self, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: Sequence[int],
                  block_size: int, k_start_blocks: Sequence[float], mu: float = 0.7, k_min: int = 0,
                  n_sink: int = 4, n_local: int = 4, beta: float = 0.2, route_scale: float = 1.0,
-                 softmax_scale: Optional[float] = None, want_lse: bool = False):
+                 softmax_scale: Optional[float] = None, want_lse: bool = False, ad_stride: int = 1):
         if not (q.is_cuda and k.is_cuda and v.is_cuda):
             raise RuntimeError("StemPrefill needs device tensors; there is no CPU path")
         assert q.dtype == k.dtype == v.dtype == torch.bfloat16
@@ -27,6 +27,7 @@ class StemPrefill:
         self.shape = sb.Shape.from_tensors(q, k, block_size, cu_seqlens)
         self.n_sink, self.n_local = int(n_sink), int(n_local)
         self.beta, self.route_scale = float(beta), float(route_scale)
+        self.ad_stride = int(ad_stride)
         self.softmax_scale = float(softmax_scale if softmax_scale is not None else q.shape[2] ** -0.5)
         self.rows, self.nbmax = sb.stem_rows(self.shape)
         budget_host, kmax = sb.stem_budget_schedule(self.shape, k_start_blocks, mu, k_min, n_sink, n_local)
@@ -35,7 +36,7 @@ class StemPrefill:
         dev = q.device
         Hq, T = q.shape[1], q.shape[0]
         self.budget = budget_host.to(dev)
-        self.workspace = torch.empty(sb.stem_workspace_bytes(self.shape), dtype=torch.uint8, device=dev)
+        self.workspace = torch.empty(sb.stem_workspace_bytes(self.shape, self.ad_stride), dtype=torch.uint8, device=dev)
         self.scores = torch.empty((Hq, self.rows, self.nbmax), dtype=torch.float32, device=dev)
         self.counts = torch.empty((Hq, self.rows), dtype=torch.int32, device=dev)
         self.indices = torch.empty((Hq, self.rows, self.kmax), dtype=torch.int32, device=dev)
@@ -43,14 +44,15 @@ class StemPrefill:
         self.lse = torch.empty((Hq, T), dtype=torch.float32, device=dev) if want_lse else None
 
     def estimate(self) -> None:
-        sb.stem_estimate(self.shape, self.q, self.k, self.v, self.beta, self.route_scale, 1,
-                         self.scores, self.workspace)
+        sb.stem_estimate(self.shape, self.q, self.k, self.v, self.beta, self.route_scale,
+                         self.ad_stride, self.scores, self.workspace)
 
     def pool(self) -> None:
-        sb.stem_pool(self.shape, self.q, self.k, self.v, self.workspace)
+        sb.stem_pool(self.shape, self.q, self.k, self.v, self.ad_stride, self.workspace)
 
     def block_scores(self) -> None:
-        sb.stem_block_scores(self.shape, self.workspace, self.beta, self.route_scale, self.scores)
+        sb.stem_block_scores(self.shape, self.workspace, self.ad_stride, self.beta, self.route_scale,
+                             self.scores)
 
     def select(self) -> None:
         sb.stem_select(self.shape, self.scores, self.budget, self.n_sink, self.n_local, self.counts,
@@ -67,11 +69,12 @@ class StemPrefill:
         return self.out
 
     def pooled(self):
-        """Views of the pooled workspace: q_bar [Hq,R,d], k_bar [Hkv,R,d], m_v [Hkv,R] (fp32)."""
-        qo, ko, mo = sb.stem_workspace_layout(self.shape)
+        """Views of the pooled workspace: q_bar [Hq,R,S,d], k_bar [Hkv,R,S,d], m_v [Hkv,R] (fp32)."""
+        S = self.ad_stride
+        qo, ko, mo = sb.stem_workspace_layout(self.shape, S)
         Hq, Hkv, d, R = self.q.shape[1], self.k.shape[1], self.q.shape[2], self.rows
         f = self.workspace
-        q_bar = f[qo:qo + 4 * Hq * R * d].view(torch.float32).view(Hq, R, d)
-        k_bar = f[ko:ko + 4 * Hkv * R * d].view(torch.float32).view(Hkv, R, d)
+        q_bar = f[qo:qo + 4 * Hq * R * S * d].view(torch.float32).view(Hq, R, S, d)
+        k_bar = f[ko:ko + 4 * Hkv * R * S * d].view(torch.float32).view(Hkv, R, S, d)
         m_v = f[mo:mo + 4 * Hkv * R].view(torch.float32).view(Hkv, R)
         return q_bar, k_bar, m_v

@@ -30,18 +30,20 @@ def host_arrays(data):
     return tuple(data[x].float().numpy() for x in "qkv")
 
 
-def device_prefill(w: wl.Workload, data, want_lse=True) -> StemPrefill:
+def device_prefill(w: wl.Workload, data, want_lse=True, ad_stride=1) -> StemPrefill:
     dev = torch.device("cuda:0")
     q, k, v = (data[x].to(dev) for x in "qkv")
     return StemPrefill(q, k, v, w.cu_seqlens, w.block_size, w.k_start_blocks, w.mu, w.k_min, w.n_sink,
-                       w.n_local, w.beta, w.route_scale, w.softmax_scale, want_lse=want_lse)
+                       w.n_local, w.beta, w.route_scale, w.softmax_scale, want_lse=want_lse,
+                       ad_stride=ad_stride)
 
 
-def oracle_estimate(w: wl.Workload, qkv):
+def oracle_estimate(w: wl.Workload, qkv, ad_stride=1):
+    """q_bar [Hq,R,S,d], k_bar [Hkv,R,S,d], m_v [Hkv,R], scores [Hq,R,NBmax] (fp64)."""
     q, k, v = qkv
-    q_bar, k_bar, m_v = so.pool_blocks(q, k, v, w.cu_seqlens, w.block_size)
+    q_bar, k_bar, m_v = so.pool_blocks(q, k, v, w.cu_seqlens, w.block_size, ad_stride)
     scores = so.oam_scores(q_bar, k_bar, m_v, w.cu_seqlens, w.block_size, w.beta, w.route_scale)
-    return q_bar[:, :, 0, :], k_bar[:, :, 0, :], m_v, scores
+    return q_bar, k_bar, m_v, scores
 
 
 def oracle_select(w: wl.Workload, scores):

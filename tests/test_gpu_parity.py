@@ -78,6 +78,41 @@ def test_tiny_4k_whole_path():
     run_both(wl.TINY_4K)
 
 
+STRIDED = {
+    # tails of 40 and 3 tokens: with S >= 4 the last block of the second sequence has empty classes
+    "tails_b64": wl.small("tails_b64", seed=31, num_q_heads=4, num_kv_heads=2, seq_lens=(1000, 67),
+                          block_size=64, k_start=(6, 2), n_sink=1, n_local=1, outliers=(2, 1)),
+    "packed_b128": SMALL["packed_b128"],
+    "long_b128": SMALL["long_b128"],
+}
+
+
+@pytest.mark.parametrize("ad_stride", [2, 4, 8, 16])
+@pytest.mark.parametrize("name", sorted(STRIDED))
+def test_anti_diagonal_strides_estimate_and_select(name, ad_stride):
+    """Stages 1-2 with S partial means per block (the strided anti-diagonal sample of the block's
+    logits); stage 3 does not depend on S."""
+    w = STRIDED[name]
+    say("case", w.name, "seed", w.seed, "ad_stride", ad_stride)
+    data = wl.generate(w)
+    qkv = pu.host_arrays(data)
+    pf = pu.device_prefill(w, data, ad_stride=ad_stride)
+    pf.estimate()
+    pf.select()
+    torch.cuda.synchronize()
+    q_bar, k_bar, m_v, scores = pu.oracle_estimate(w, qkv, ad_stride)
+    assert q_bar.shape[2] == ad_stride
+    pu.check_pooled(pf, q_bar, k_bar, m_v)
+    err = pu.check_scores(pf.scores.cpu().numpy(), scores)
+    budget, counts, indices = pu.oracle_select(w, scores)
+    pu.check_lists(w, pf.counts.cpu().numpy(), pf.indices.cpu().numpy(), counts, indices, scores, say)
+    # the strided sample is a different estimate from the block mean, not a relabelling of it
+    mean_scores = pu.oracle_estimate(w, qkv, 1)[3]
+    fin = np.isfinite(scores)
+    assert np.abs(scores[fin] - mean_scores[fin]).max() > 1e-3
+    say("%s S=%d: score err %.3g" % (w.name, ad_stride, err))
+
+
 def test_select_is_bit_exact_on_shared_fp32_scores():
     """Stage 2 alone, on one fp32 score tensor given to both sides (exactly representable in fp64, so
     no near-tie allowance), with planted exact ties, +-0, and equal rows."""

@@ -33,10 +33,16 @@ def test_rows_and_workspace():
     shape = make_shape([0, 100, 100, 740], B=64)
     assert sb.stem_rows(shape) == (2 + 0 + 10, 10)
     assert sb.stem_rows(shape) == so.total_rows([0, 100, 100, 740], 64)
-    q_off, k_off, m_off = sb.stem_workspace_layout(shape)
-    total = sb.stem_workspace_bytes(shape)
-    assert q_off == 0 and k_off >= 4 * 12 * 128 * 4 and m_off >= k_off + 2 * 12 * 128 * 4
-    assert total >= m_off + 2 * 12 * 4 and k_off % 256 == 0 and m_off % 256 == 0
+    for S in (1, 2, 4, 8, 16):
+        q_off, k_off, m_off = sb.stem_workspace_layout(shape, S)
+        total = sb.stem_workspace_bytes(shape, S)
+        assert q_off == 0 and k_off >= 4 * 12 * S * 128 * 4 and m_off >= k_off + 2 * 12 * S * 128 * 4
+        assert total >= m_off + 2 * 12 * 4 and k_off % 256 == 0 and m_off % 256 == 0
+    n = ctypes.c_size_t()
+    L = sb.lib()
+    for S, want in ((0, sb.STEM_ERR_INVALID_ARG), (-2, sb.STEM_ERR_INVALID_ARG), (3, sb.STEM_ERR_INVALID_ARG),
+                    (32, sb.STEM_ERR_UNSUPPORTED), (64, sb.STEM_ERR_UNSUPPORTED), (128, sb.STEM_ERR_INVALID_ARG)):
+        assert L.stem_workspace_bytes(shape.ref(), S, ctypes.byref(n)) == want, S
 
 
 @pytest.mark.parametrize("cu,B,ks,mu,k_min,n_sink,n_local", [
@@ -77,23 +83,27 @@ def test_bad_arguments_are_rejected_on_the_host():
     good = make_shape([0, 640])
     n = ctypes.c_size_t()
     # shape errors
-    assert L.stem_workspace_bytes(make_shape([0, 640], Hq=3, Hkv=2).ref(), ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_workspace_bytes(make_shape([0, 640], d=64).ref(), ctypes.byref(n)) == sb.STEM_ERR_UNSUPPORTED
-    assert L.stem_workspace_bytes(make_shape([0, 640], B=32).ref(), ctypes.byref(n)) == sb.STEM_ERR_UNSUPPORTED
-    assert L.stem_workspace_bytes(make_shape([0, 640, 600]).ref(), ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_workspace_bytes(make_shape([1, 640]).ref(), ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_workspace_bytes(make_shape(list(range(0, 66 * 64, 64))).ref(), ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_workspace_bytes(make_shape([0, 64 * 5000]).ref(), ctypes.byref(n)) == sb.STEM_ERR_UNSUPPORTED
+    assert L.stem_workspace_bytes(make_shape([0, 640], Hq=3, Hkv=2).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_workspace_bytes(make_shape([0, 640], d=64).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_UNSUPPORTED
+    assert L.stem_workspace_bytes(make_shape([0, 640], B=32).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_UNSUPPORTED
+    assert L.stem_workspace_bytes(make_shape([0, 640, 600]).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_workspace_bytes(make_shape([1, 640]).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_workspace_bytes(make_shape(list(range(0, 66 * 64, 64))).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_workspace_bytes(make_shape([0, 64 * 5000]).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_UNSUPPORTED
     bad_stride = sb.Shape(4, 2, 128, 64, [0, 640], (4 * 128 + 4, 128), (2 * 128, 128))
-    assert L.stem_workspace_bytes(bad_stride.ref(), ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_workspace_bytes(None, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_workspace_bytes(bad_stride.ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_workspace_bytes(None, 1, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
     # null / misaligned device pointers, short workspace: refused before any launch
-    assert L.stem_pool(good.ref(), None, None, None, None, 0, None) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_pool(good.ref(), 0x1000, 0x1000, 0x1008, 0x1000, 1 << 30, None) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_pool(good.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 16, None) == sb.STEM_ERR_WORKSPACE
-    assert L.stem_estimate(good.ref(), 0x1000, 0x1000, 0x1000, 0.2, 1.0, 2, 0x1000, 0x1000, 1 << 30, None) == sb.STEM_ERR_UNSUPPORTED
+    assert L.stem_pool(good.ref(), None, None, None, 1, None, 0, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_pool(good.ref(), 0x1000, 0x1000, 0x1008, 1, 0x1000, 1 << 30, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_pool(good.ref(), 0x1000, 0x1000, 0x1000, 1, 0x1000, 16, None) == sb.STEM_ERR_WORKSPACE
+    assert L.stem_pool(good.ref(), 0x1000, 0x1000, 0x1000, 5, 0x1000, 1 << 30, None) == sb.STEM_ERR_INVALID_ARG
+    # a workspace sized for block means is too small for four partial means per block
+    small_ws = sb.stem_workspace_bytes(good, 1)
+    assert L.stem_pool(good.ref(), 0x1000, 0x1000, 0x1000, 4, 0x1000, small_ws, None) == sb.STEM_ERR_WORKSPACE
+    assert L.stem_estimate(good.ref(), 0x1000, 0x1000, 0x1000, 0.2, 1.0, 32, 0x1000, 0x1000, 1 << 30, None) == sb.STEM_ERR_UNSUPPORTED
     assert L.stem_estimate(good.ref(), 0x1000, 0x1000, 0x1000, 0.2, 1.0, 0, 0x1000, 0x1000, 1 << 30, None) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_block_scores(good.ref(), 0x1000, 1 << 30, float("nan"), 1.0, 0x1000, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_block_scores(good.ref(), 0x1000, 1 << 30, 1, float("nan"), 1.0, 0x1000, None) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_select(good.ref(), 0x1000, 0x1000, 1, 1, 0x1000, None, 8, None) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_select(good.ref(), 0x1000, 0x1000, -1, 1, 0x1000, 0x1000, 8, None) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_select(good.ref(), 0x1000, 0x1000, 3, 3, 0x1000, 0x1000, 4, None) == sb.STEM_ERR_INVALID_ARG
@@ -106,7 +116,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     # an empty batch entry list is fine on the host and launches nothing
     empty = make_shape([0, 0])
     assert sb.stem_rows(empty) == (0, 0)
-    assert L.stem_pool(empty.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 1 << 20, None) == sb.STEM_OK
+    assert L.stem_pool(empty.ref(), 0x1000, 0x1000, 0x1000, 1, 0x1000, 1 << 20, None) == sb.STEM_OK
     assert L.stem_sparse_attn(empty.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 4, 0.1, 0x1000, None, None) == sb.STEM_OK
     with pytest.raises(sb.StemError):
         sb.stem_rows(make_shape([0, 640], d=64))
