@@ -26,8 +26,18 @@
  *     rows of all sequences are numbered consecutively: R = sum of blocks ("rows"), NBmax = the
  *     longest sequence in blocks.  Key-block indices are 0-based and local to the row's sequence;
  *     row i of a sequence may use key blocks 0..i.
+ *   - Chunked pre-filling (a long prompt processed piece by piece against its growing KV cache):
+ *     with host_chunk_start / host_chunk_end set, a call covers of sequence s only the queries at
+ *     positions chunk_start[s] .. chunk_end[s] - 1 (relative to the sequence's first token) and the
+ *     keys before chunk_end[s].  Then Q, O and lse hold the chunks' tokens only, packed in sequence
+ *     order (T = sum of chunk lengths), while K and V keep the layout given by host_cu_seqlens
+ *     (rows at or after chunk_end[s] are not read).  R counts the chunks' query blocks, NBmax the
+ *     most key blocks a row of the call can see, and rows keep their block index i inside the
+ *     sequence for the schedule, the causal limit and the windows, so the chunks of a prompt give
+ *     the rows of the one-piece call.  chunk_start must be a multiple of B, chunk_end a multiple
+ *     of B or the sequence's length; an empty chunk (start == end) contributes nothing.
  *   - Supported: head_dim 128; block_size 64 or 128; 1 <= batch <= STEM_MAX_BATCH; Hq a multiple
- *     of Hkv; NBmax <= STEM_MAX_BLOCKS.
+ *     of Hkv; at most STEM_MAX_BLOCKS blocks per sequence.
  */
 #ifndef STEM_H
 #define STEM_H
@@ -59,6 +69,8 @@ typedef struct stem_shape {
     int64_t q_stride_head;           /* elements between consecutive heads of Q (and of O)          */
     int64_t kv_stride_token;         /* same for K and V (they share strides)                       */
     int64_t kv_stride_head;
+    const int32_t* host_chunk_start; /* HOST [batch] or NULL: first query position of the call      */
+    const int32_t* host_chunk_end;   /* HOST [batch] or NULL (both or neither): one past the last   */
 } stem_shape;
 
 /* Library version: major * 10000 + minor * 100 + patch. */
@@ -67,7 +79,8 @@ int stem_version(void);
 /* Static, NUL-terminated description of a status code. */
 const char* stem_strerror(int status);
 
-/* R (total query-block rows) and NBmax (blocks of the longest sequence) of a shape. */
+/* R (query-block rows of the call) and NBmax (most key blocks a row can see: the blocks of the
+ * longest sequence, or up to the latest chunk end) of a shape. */
 int stem_rows(const stem_shape* shape, int32_t* host_total_rows, int32_t* host_max_blocks);
 
 /*
@@ -83,8 +96,11 @@ int stem_rows(const stem_shape* shape, int32_t* host_total_rows, int32_t* host_m
  */
 
 /* Bytes of device workspace stem_estimate / stem_pool need for this shape and ad_stride S.
- * Layout (fp32):
- *   q_bar [Hq, R, S, d] | k_bar [Hkv, R, S, d] | m_v [Hkv, R]   (each part 256-byte aligned). */
+ * Layout (fp32), Rk = blocks of all sequences (whole sequences, whatever the chunk):
+ *   k_bar [Hkv, Rk, S, d] | m_v [Hkv, Rk] | q_bar [Hq, R, S, d]   (each part 256-byte aligned).
+ * The key parts come first and do not depend on the chunk: a caller that keeps one workspace
+ * (sized for the largest chunk) across the chunks of a prompt keeps the pooled keys of earlier
+ * chunks, and stem_pool only pools the blocks of the current chunk. */
 int stem_workspace_bytes(const stem_shape* shape, int32_t ad_stride, size_t* host_bytes);
 
 /* Byte offsets of the three workspace parts (for callers that want to look at them). */
@@ -97,7 +113,8 @@ int stem_workspace_layout(const stem_shape* shape, int32_t ad_stride, size_t* ho
  *     k(i)     = floor( ks - (ks * (1 - mu) / n) * (i + 1) + 1e-9 )
  *     k_eff(i) = min( i + 1, max( k(i), k_min, |forced(i)| ) )
  * where forced(i) = first n_sink blocks united with the last n_local causal blocks (diagonal
- * included).  mu = 1 gives the uniform top-k control.  Writes host_budget[R] and, if not NULL,
+ * included).  n counts the whole sequence also when the call covers a chunk of it (whose rows
+ * keep their index i).  mu = 1 gives the uniform top-k control.  Writes host_budget[R] and, if not NULL,
  * the largest entry to *host_kmax.  Requires 0 < mu <= 1, ks >= 0, k_min, n_sink, n_local >= 0.
  */
 int stem_budget_schedule(const stem_shape* shape, const double* host_k_start_blocks, double mu,
@@ -105,11 +122,13 @@ int stem_budget_schedule(const stem_shape* shape, const double* host_k_start_blo
                          int32_t* host_budget, int32_t* host_kmax);
 
 /*
- * Algorithm 1 step 1: pooled block representations into the workspace (layout above).
+ * Algorithm 1 step 1: pooled block representations into the workspace (layout above), for the
+ * blocks of the call's chunks (all blocks without chunks).  With kr = the block's row among all
+ * blocks of all sequences:
  *   q_bar[h, r, a, :] = mean of Q[t, h, :] over the valid tokens t of row r's block whose in-block
  *                       position is congruent to a modulo S (zeros if there is none)     (fp32)
- *   k_bar[g, r, a, :] = the same for K
- *   m_v[g, r]         = max over the block's valid tokens of ln ||V[t, g, :]||_2  (-inf if all zero)
+ *   k_bar[g, kr, a, :] = the same for K
+ *   m_v[g, kr]        = max over the block's valid tokens of ln ||V[t, g, :]||_2  (-inf if all zero)
  */
 int stem_pool(const stem_shape* shape, const void* q, const void* k, const void* v,
               int32_t ad_stride, void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -37,6 +37,8 @@ class stem_shape(ctypes.Structure):
         ("host_cu_seqlens", ctypes.POINTER(ctypes.c_int32)),
         ("q_stride_token", ctypes.c_int64), ("q_stride_head", ctypes.c_int64),
         ("kv_stride_token", ctypes.c_int64), ("kv_stride_head", ctypes.c_int64),
+        ("host_chunk_start", ctypes.POINTER(ctypes.c_int32)),
+        ("host_chunk_end", ctypes.POINTER(ctypes.c_int32)),
     ]
 
 
@@ -96,22 +98,35 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
 
 
 class Shape:
-    """Owns the ctypes stem_shape and the host cu_seqlens array it points to."""
+    """Owns the ctypes stem_shape and the host arrays it points to.  chunk = (starts, ends): per
+    sequence, the query positions of a chunked call (None: whole sequences)."""
 
     def __init__(self, num_q_heads: int, num_kv_heads: int, head_dim: int, block_size: int,
-                 cu_seqlens: Sequence[int], q_strides: Tuple[int, int], kv_strides: Tuple[int, int]):
+                 cu_seqlens: Sequence[int], q_strides: Tuple[int, int], kv_strides: Tuple[int, int],
+                 chunk: Optional[Tuple[Sequence[int], Sequence[int]]] = None):
+        i32p = ctypes.POINTER(ctypes.c_int32)
         self._cu = (ctypes.c_int32 * len(cu_seqlens))(*[int(x) for x in cu_seqlens])
-        self.c = stem_shape(num_q_heads, num_kv_heads, head_dim, block_size, len(cu_seqlens) - 1,
-                            ctypes.cast(self._cu, ctypes.POINTER(ctypes.c_int32)),
-                            q_strides[0], q_strides[1], kv_strides[0], kv_strides[1])
+        batch = len(cu_seqlens) - 1
+        if chunk is not None:
+            assert len(chunk[0]) == batch and len(chunk[1]) == batch
+            self._cs = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in chunk[0]])
+            self._ce = (ctypes.c_int32 * max(batch, 1))(*[int(x) for x in chunk[1]])
+            cs, ce = ctypes.cast(self._cs, i32p), ctypes.cast(self._ce, i32p)
+        else:
+            cs, ce = i32p(), i32p()
+        self.c = stem_shape(num_q_heads, num_kv_heads, head_dim, block_size, batch,
+                            ctypes.cast(self._cu, i32p),
+                            q_strides[0], q_strides[1], kv_strides[0], kv_strides[1], cs, ce)
         self.cu_seqlens = [int(x) for x in cu_seqlens]
+        self.chunk = None if chunk is None else ([int(x) for x in chunk[0]], [int(x) for x in chunk[1]])
 
     @classmethod
-    def from_tensors(cls, q: torch.Tensor, k: torch.Tensor, block_size: int, cu_seqlens: Sequence[int]):
-        """q [T,Hq,d], k [T,Hkv,d] (any token/head strides, last dim contiguous)."""
+    def from_tensors(cls, q: torch.Tensor, k: torch.Tensor, block_size: int, cu_seqlens: Sequence[int],
+                     chunk: Optional[Tuple[Sequence[int], Sequence[int]]] = None):
+        """q [T,Hq,d], k [Tk,Hkv,d] (any token/head strides, last dim contiguous)."""
         assert q.dim() == 3 and k.dim() == 3 and q.stride(2) == 1 and k.stride(2) == 1
         return cls(q.shape[1], k.shape[1], q.shape[2], block_size, cu_seqlens,
-                   (q.stride(0), q.stride(1)), (k.stride(0), k.stride(1)))
+                   (q.stride(0), q.stride(1)), (k.stride(0), k.stride(1)), chunk)
 
     def ref(self):
         return ctypes.byref(self.c)

@@ -33,28 +33,50 @@ int make_problem(const stem_shape* s, Problem* out) {
     p.kv_st = s->kv_stride_token;
     p.kv_sh = s->kv_stride_head;
     if (s->host_cu_seqlens[0] != 0) return STEM_ERR_INVALID_ARG;
+    if ((s->host_chunk_start == nullptr) != (s->host_chunk_end == nullptr)) return STEM_ERR_INVALID_ARG;
     p.seq.batch = p.batch;
-    int64_t rows = 0;
+    int64_t rows = 0, key_rows = 0, q_tokens = 0;
     int32_t nbmax = 0;
     for (int i = 0; i < p.batch; ++i) {
         int64_t lo = s->host_cu_seqlens[i], hi = s->host_cu_seqlens[i + 1];
         if (hi < lo) return STEM_ERR_INVALID_ARG;
-        int64_t nb = (hi - lo + p.B - 1) / p.B;
+        const int64_t len = hi - lo;
+        const int64_t nb = (len + p.B - 1) / p.B;
         if (nb > STEM_MAX_BLOCKS) return STEM_ERR_UNSUPPORTED;
+        // the chunk of this call: block-aligned start; the end is block-aligned or the sequence's end
+        int64_t cs = 0, ce = len;
+        if (s->host_chunk_start) {
+            cs = s->host_chunk_start[i];
+            ce = s->host_chunk_end[i];
+            if (cs < 0 || ce < cs || ce > len) return STEM_ERR_INVALID_ARG;
+            if (ce > cs && (cs % p.B || (ce % p.B && ce != len))) return STEM_ERR_INVALID_ARG;
+        }
+        const int64_t first = cs / p.B, seen = (ce + p.B - 1) / p.B;   // blocks before / up to the chunk's end
         p.seq.tok_start[i] = (int32_t)lo;
         p.seq.row_start[i] = (int32_t)rows;
-        rows += nb;
-        if (nb > nbmax) nbmax = (int32_t)nb;
+        p.seq.q_tok_start[i] = (int32_t)q_tokens;
+        p.seq.key_row_start[i] = (int32_t)key_rows;
+        p.seq.first_block[i] = (int32_t)first;
+        p.seq.kv_end[i] = (int32_t)(lo + ce);
+        rows += ce > cs ? seen - first : 0;
+        q_tokens += ce - cs;
+        key_rows += nb;
+        if (ce > cs && seen > nbmax) nbmax = (int32_t)seen;
     }
-    if (rows > (int64_t)1 << 24) return STEM_ERR_UNSUPPORTED;
-    p.seq.tok_start[p.batch] = s->host_cu_seqlens[p.batch];
-    p.seq.row_start[p.batch] = (int32_t)rows;
-    for (int i = p.batch + 1; i <= STEM_MAX_BATCH; ++i) {
-        p.seq.tok_start[i] = p.seq.tok_start[p.batch];
-        p.seq.row_start[i] = p.seq.row_start[p.batch];
+    if (rows > (int64_t)1 << 24 || key_rows > (int64_t)1 << 24) return STEM_ERR_UNSUPPORTED;
+    for (int i = p.batch; i <= STEM_MAX_BATCH; ++i) {
+        p.seq.tok_start[i] = s->host_cu_seqlens[p.batch];
+        p.seq.row_start[i] = (int32_t)rows;
+        p.seq.q_tok_start[i] = (int32_t)q_tokens;
+        p.seq.key_row_start[i] = (int32_t)key_rows;
+        if (i < STEM_MAX_BATCH) {
+            p.seq.first_block[i] = 0;
+            p.seq.kv_end[i] = s->host_cu_seqlens[p.batch];
+        }
     }
-    p.T = s->host_cu_seqlens[p.batch];
+    p.T = (int32_t)q_tokens;
     p.R = (int32_t)rows;
+    p.Rk = (int32_t)key_rows;
     p.NBmax = nbmax;
     *out = p;
     return STEM_OK;
@@ -70,10 +92,12 @@ int check_ad_stride(const Problem& p, int ad_stride) {
 
 WorkspaceLayout workspace_layout(const Problem& p, int ad_stride) {
     WorkspaceLayout w;
-    w.q_bar = 0;
-    w.k_bar = align256(w.q_bar + sizeof(float) * (size_t)p.Hq * p.R * ad_stride * kHeadDim);
-    w.m_v = align256(w.k_bar + sizeof(float) * (size_t)p.Hkv * p.R * ad_stride * kHeadDim);
-    w.total = align256(w.m_v + sizeof(float) * (size_t)p.Hkv * p.R);
+    // the key parts come first and depend on the sequences only, not on the chunk: a caller that
+    // keeps the workspace between the chunks of a prompt finds the earlier chunks' keys in place
+    w.k_bar = 0;
+    w.m_v = align256(w.k_bar + sizeof(float) * (size_t)p.Hkv * p.Rk * ad_stride * kHeadDim);
+    w.q_bar = align256(w.m_v + sizeof(float) * (size_t)p.Hkv * p.Rk);
+    w.total = align256(w.q_bar + sizeof(float) * (size_t)p.Hq * p.R * ad_stride * kHeadDim);
     if (w.total == 0) w.total = 256;
     return w;
 }
@@ -141,12 +165,14 @@ int stem_budget_schedule(const stem_shape* shape, const double* host_k_start_blo
         if (!(host_k_start_blocks[s] >= 0.0) || host_k_start_blocks[s] > 1e9) return STEM_ERR_INVALID_ARG;
     int32_t kmax = 0;
     for (int s = 0; s < p.batch; ++s) {
-        const int32_t n = p.seq.row_start[s + 1] - p.seq.row_start[s];
+        // n of Eq. 3 is the whole sequence; the call's rows are blocks first .. first + rows - 1 of it
+        const int32_t n = p.seq.key_row_start[s + 1] - p.seq.key_row_start[s];
+        const int32_t first = p.seq.first_block[s], rows = p.seq.row_start[s + 1] - p.seq.row_start[s];
         const double ks = host_k_start_blocks[s];
         // per-row decrement of Eq. 3; volatile keeps the compiler from contracting the
         // multiply-subtract below into one fused operation
         volatile double step = n > 0 ? (ks * (1.0 - mu)) / (double)n : 0.0;
-        for (int32_t i = 0; i < n; ++i) {
+        for (int32_t i = first; i < first + rows; ++i) {
             volatile double dec = step * (double)(i + 1);
             int64_t k = (int64_t)std::floor(ks - dec + 1e-9);
             const int32_t head = n_sink < i + 1 ? n_sink : i + 1;             // blocks 0..head-1
@@ -155,7 +181,7 @@ int stem_budget_schedule(const stem_shape* shape, const double* host_k_start_blo
             if (k < k_min) k = k_min;
             if (k < forced) k = forced;
             if (k > i + 1) k = i + 1;
-            host_budget[p.seq.row_start[s] + i] = (int32_t)k;
+            host_budget[p.seq.row_start[s] + (i - first)] = (int32_t)k;
             if (k > kmax) kmax = (int32_t)k;
         }
     }

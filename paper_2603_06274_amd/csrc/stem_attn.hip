@@ -134,16 +134,18 @@ __device__ __forceinline__ void sparse_attn_body(
     const int h = g * G + rem % G;
 
     const int s = seq_of_row(seq, r);
-    const int i = r - seq.row_start[s];
-    const int seq_lo = seq.tok_start[s], seq_hi = seq.tok_start[s + 1];
-    const int tok_q0 = seq_lo + i * B;
+    const int ic = r - seq.row_start[s];               // row inside the call's chunk of the sequence
+    const int i = seq.first_block[s] + ic;             // block index in the sequence
+    const int seq_lo = seq.tok_start[s], seq_hi = seq.kv_end[s];   // key token rows the call may read
+    const int tok_q0 = seq.q_tok_start[s] + ic * B;    // Q, O and lse hold the chunk's tokens only
+    const int q_hi = seq.q_tok_start[s + 1];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, hi = lane >> 5;
     const int qrow = w * 32 + col;                     // query row inside the block
     const int tok_q = tok_q0 + qrow;
-    const bool q_valid = tok_q < seq_hi;
+    const bool q_valid = tok_q < q_hi;
 
     const int cnt = min(counts[(int64_t)h * R + r], kmax);
     const int32_t* list = indices + ((int64_t)h * R + r) * kmax;

@@ -11,16 +11,25 @@ namespace stem {
 constexpr int kHeadDim = 128;
 
 // Packed-sequence table, passed to kernels by value (no device-side cu_seqlens read, no sync).
+// A call covers, of every sequence, the query blocks of one chunk [chunk_start, chunk_end) (the
+// whole sequence unless the shape says otherwise) and the keys before chunk_end.
 struct SeqTable {
     int32_t batch;
-    int32_t tok_start[STEM_MAX_BATCH + 1];   // cu_seqlens
-    int32_t row_start[STEM_MAX_BATCH + 1];   // prefix sums of blocks per sequence
+    int32_t tok_start[STEM_MAX_BATCH + 1];      // cu_seqlens: token rows of K and V
+    int32_t row_start[STEM_MAX_BATCH + 1];      // prefix sums of the call's query-block rows
+    int32_t q_tok_start[STEM_MAX_BATCH + 1];    // prefix sums of the call's query tokens (rows of Q, O, lse)
+    int32_t key_row_start[STEM_MAX_BATCH + 1];  // prefix sums of all blocks per sequence (rows of k_bar, m_v)
+    int32_t first_block[STEM_MAX_BATCH];        // index in its sequence of the first query block of the call
+    int32_t kv_end[STEM_MAX_BATCH];             // token row of K/V one past the last key of the call
 };
 
 // Everything the host derives from a stem_shape.
 struct Problem {
     int32_t Hq, Hkv, G, B, batch;
-    int32_t T, R, NBmax;
+    int32_t T;        // query tokens of the call (rows of Q, O, lse)
+    int32_t R;        // query-block rows of the call
+    int32_t Rk;       // blocks of all sequences (rows of k_bar, m_v)
+    int32_t NBmax;    // most key blocks any row of the call can see
     int64_t q_st, q_sh, kv_st, kv_sh;
     SeqTable seq;
 };

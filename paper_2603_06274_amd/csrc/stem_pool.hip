@@ -20,24 +20,28 @@ template <int B>
 __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     float* __restrict__ q_bar, float* __restrict__ k_bar, float* __restrict__ m_v, SeqTable seq,
-    int Hq, int Hkv, int R, int S, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh) {
+    int Hq, int Hkv, int R, int Rk, int S, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh) {
     constexpr int kTok = B / 16;                       // tokens per thread
     const int slots = Hq + 2 * Hkv;
     const int r = blockIdx.x / slots;
     const int slot = blockIdx.x - r * slots;
     const int s = seq_of_row(seq, r);
-    const int tok0 = seq.tok_start[s] + (r - seq.row_start[s]) * B;
-    const int n_valid = min(B, seq.tok_start[s + 1] - tok0);
+    const int ic = r - seq.row_start[s];               // row inside the call's chunk of the sequence
+    const int i = seq.first_block[s] + ic;             // block index in the sequence
+    const int kv_tok0 = seq.tok_start[s] + i * B;      // first token row of the block in K and V
+    const int q_tok0 = seq.q_tok_start[s] + ic * B;    // and in Q, which holds the chunk's tokens only
+    const int n_valid = min(B, seq.kv_end[s] - kv_tok0);
+    const int key_row = seq.key_row_start[s] + i;      // row of k_bar and m_v
 
     const uint16_t* src;
     int64_t st;
-    int kind, head;                                    // 0: Q, 1: K, 2: V
+    int kind, head, tok0;                              // 0: Q, 1: K, 2: V
     if (slot < Hq) {
-        kind = 0; head = slot; src = q + (int64_t)head * q_sh; st = q_st;
+        kind = 0; head = slot; src = q + (int64_t)head * q_sh; st = q_st; tok0 = q_tok0;
     } else if (slot < Hq + Hkv) {
-        kind = 1; head = slot - Hq; src = k + (int64_t)head * kv_sh; st = kv_st;
+        kind = 1; head = slot - Hq; src = k + (int64_t)head * kv_sh; st = kv_st; tok0 = kv_tok0;
     } else {
-        kind = 2; head = slot - Hq - Hkv; src = v + (int64_t)head * kv_sh; st = kv_st;
+        kind = 2; head = slot - Hq - Hkv; src = v + (int64_t)head * kv_sh; st = kv_st; tok0 = kv_tok0;
     }
 
     const int tid = threadIdx.x;
@@ -68,7 +72,8 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) part[tl][c * 8 + e] = acc[e];
         __syncthreads();
-        float* dst = (kind == 0 ? q_bar : k_bar) + ((int64_t)head * R + r) * S * kHeadDim;
+        float* dst = kind == 0 ? q_bar + ((int64_t)head * R + r) * S * kHeadDim
+                               : k_bar + ((int64_t)head * Rk + key_row) * S * kHeadDim;
         for (int o = tid; o < S * kHeadDim; o += kPoolThreads) {
             const int a = o >> 7, col = o & (kHeadDim - 1);   // residue class, column
             float sum = 0.f;
@@ -99,7 +104,7 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
         if (tid == 0) {
             float m = fmaxf(fmaxf(vmax[0], vmax[1]), fmaxf(vmax[2], vmax[3]));
             // max_t ln ||v_t|| = 0.5 ln max_t ||v_t||^2 ; ln 0 = -inf
-            m_v[(int64_t)head * R + r] = 0.5f * logf(m);
+            m_v[(int64_t)head * Rk + key_row] = 0.5f * logf(m);
         }
     }
 }
@@ -115,10 +120,10 @@ int launch_pool(const Problem& p, int ad_stride, const void* q, const void* k, c
     const uint16_t* vv = static_cast<const uint16_t*>(v);
     if (p.B == 128)
         hipLaunchKernelGGL(pool_kernel<128>, grid, block, 0, stream, qq, kk, vv, q_bar, k_bar, m_v,
-                           p.seq, p.Hq, p.Hkv, p.R, ad_stride, p.q_st, p.q_sh, p.kv_st, p.kv_sh);
+                           p.seq, p.Hq, p.Hkv, p.R, p.Rk, ad_stride, p.q_st, p.q_sh, p.kv_st, p.kv_sh);
     else
         hipLaunchKernelGGL(pool_kernel<64>, grid, block, 0, stream, qq, kk, vv, q_bar, k_bar, m_v,
-                           p.seq, p.Hq, p.Hkv, p.R, ad_stride, p.q_st, p.q_sh, p.kv_st, p.kv_sh);
+                           p.seq, p.Hq, p.Hkv, p.R, p.Rk, ad_stride, p.q_st, p.q_sh, p.kv_st, p.kv_sh);
     return check_launch();
 }
 

@@ -22,14 +22,17 @@ struct TileTable {
 
 __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
     const float* __restrict__ q_bar, const float* __restrict__ k_bar, const float* __restrict__ m_v,
-    float* __restrict__ scores, SeqTable seq, TileTable tiles, int R, int NBmax, int G, int S,
+    float* __restrict__ scores, SeqTable seq, TileTable tiles, int R, int Rk, int NBmax, int G, int S,
     float beta, float route_scale) {
     // sequence and local row tile of this workgroup
     int s = 0;
     for (int x = 1; x < seq.batch; ++x) s = ((int)blockIdx.x >= tiles.tile_start[x]) ? x : s;
     const int row0 = seq.row_start[s];
-    const int n = seq.row_start[s + 1] - row0;         // blocks of this sequence
-    const int i0 = ((int)blockIdx.x - tiles.tile_start[s]) * kTile;
+    const int n_rows = seq.row_start[s + 1] - row0;    // query-block rows of this sequence in the call
+    const int first = seq.first_block[s];              // block index of the first of them
+    const int n = first + n_rows;                      // key blocks the call can see
+    const int krow0 = seq.key_row_start[s];
+    const int i0 = ((int)blockIdx.x - tiles.tile_start[s]) * kTile;   // first row of the tile, call-local
     const int j0 = blockIdx.y * kTile;
     const int h = blockIdx.z;
     const int g = h / G;
@@ -39,11 +42,11 @@ __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
     float* out = scores + ((int64_t)h * R + row0) * NBmax;
     const float neg_inf = -__builtin_huge_valf();
 
-    if (j0 > i0 + kTile - 1) {                         // entirely above the diagonal
+    if (j0 > first + i0 + kTile - 1) {                 // entirely above the diagonal
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
             const int i = i0 + ti * 4 + x;
-            if (i >= n) continue;
+            if (i >= n_rows) continue;
 #pragma unroll
             for (int y = 0; y < 4; ++y) {
                 const int j = j0 + tj * 4 + y;
@@ -64,7 +67,7 @@ __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
 
     const int depth = S * kHeadDim;                    // floats per pooled block
     const float* a_src = q_bar + ((int64_t)h * R + row0) * depth;
-    const float* b_src = k_bar + ((int64_t)g * R + row0) * depth;
+    const float* b_src = k_bar + ((int64_t)g * Rk + krow0) * depth;
 
     for (int kc = 0; kc < depth; kc += kChunk) {
         // a chunk lies inside one residue class a of the query block; its partner is class S-1-a
@@ -75,7 +78,7 @@ __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
             const int idx = tid + kScoreThreads * u;
             const int row = idx >> 3, c4 = (idx & 7) * 4;
             float4 av = make_float4(0.f, 0.f, 0.f, 0.f), bv = av;
-            if (i0 + row < n) av = *reinterpret_cast<const float4*>(a_src + (int64_t)(i0 + row) * depth + kc + c4);
+            if (i0 + row < n_rows) av = *reinterpret_cast<const float4*>(a_src + (int64_t)(i0 + row) * depth + kc + c4);
             if (j0 + row < n) bv = *reinterpret_cast<const float4*>(b_src + (int64_t)(j0 + row) * depth + kb + c4);
             a_s[c4 + 0][row] = av.x; a_s[c4 + 1][row] = av.y; a_s[c4 + 2][row] = av.z; a_s[c4 + 3][row] = av.w;
             b_s[c4 + 0][row] = bv.x; b_s[c4 + 1][row] = bv.y; b_s[c4 + 2][row] = bv.z; b_s[c4 + 3][row] = bv.w;
@@ -99,17 +102,17 @@ __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
 #pragma unroll
     for (int y = 0; y < 4; ++y) {
         const int j = j0 + tj * 4 + y;
-        mag[y] = (j < n) ? beta * fmaxf(0.f, m_v[(int64_t)g * R + row0 + j]) : 0.f;
+        mag[y] = (j < n) ? beta * fmaxf(0.f, m_v[(int64_t)g * Rk + krow0 + j]) : 0.f;
     }
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
         const int i = i0 + ti * 4 + x;
-        if (i >= n) continue;
+        if (i >= n_rows) continue;
 #pragma unroll
         for (int y = 0; y < 4; ++y) {
             const int j = j0 + tj * 4 + y;
             if (j >= NBmax) continue;
-            out[(int64_t)i * NBmax + j] = (j <= i) ? fmaf(route_scale / (float)S, acc[x][y], mag[y]) : neg_inf;
+            out[(int64_t)i * NBmax + j] = (j <= first + i) ? fmaf(route_scale / (float)S, acc[x][y], mag[y]) : neg_inf;
         }
     }
 }
@@ -127,7 +130,7 @@ int launch_block_scores(const Problem& p, int ad_stride, const float* q_bar, con
     if (p.Hq > 65535) return STEM_ERR_UNSUPPORTED;
     dim3 grid(total, (p.NBmax + kTile - 1) / kTile, p.Hq), block(kScoreThreads);
     hipLaunchKernelGGL(block_scores_kernel, grid, block, 0, stream, q_bar, k_bar, m_v, scores, p.seq,
-                       tiles, p.R, p.NBmax, p.G, ad_stride, beta, route_scale);
+                       tiles, p.R, p.Rk, p.NBmax, p.G, ad_stride, beta, route_scale);
     return check_launch();
 }
 

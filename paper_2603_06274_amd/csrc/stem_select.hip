@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     const int h = (int)(item / R);
     const int r = (int)(item - (int64_t)h * R);
     const int s = seq_of_row(seq, r);
-    const int i = r - seq.row_start[s];
+    const int i = seq.first_block[s] + (r - seq.row_start[s]);   // block index in the sequence
 
     const int fs = min(n_sink, i + 1);                 // forced head: blocks [0, fs)
     const int fe = max(fs, i - n_local + 1);           // forced tail: blocks [fe, i]

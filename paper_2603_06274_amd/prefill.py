@@ -12,19 +12,23 @@ from . import binding as sb
 class StemPrefill:
     """One attention layer's Stem pre-filling path on one GPU.
 
-    q [T,Hq,d], k and v [T,Hkv,d]: bf16 CUDA tensors (k and v with equal strides).
+    q [T,Hq,d], k and v [Tk,Hkv,d]: bf16 CUDA tensors (k and v with equal strides).  With
+    chunk = (starts, ends), q holds only the tokens of each sequence's chunk (T = their sum) while
+    k and v keep all Tk = cu_seqlens[-1] rows; pass the same `workspace` to the calls of one
+    prompt so that the pooled keys of earlier chunks are kept.
     """
 
     def __init__(self, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: Sequence[int],
                  block_size: int, k_start_blocks: Sequence[float], mu: float = 0.7, k_min: int = 0,
                  n_sink: int = 4, n_local: int = 4, beta: float = 0.2, route_scale: float = 1.0,
-                 softmax_scale: Optional[float] = None, want_lse: bool = False, ad_stride: int = 1):
+                 softmax_scale: Optional[float] = None, want_lse: bool = False, ad_stride: int = 1,
+                 chunk=None, workspace: Optional[torch.Tensor] = None):
         if not (q.is_cuda and k.is_cuda and v.is_cuda):
             raise RuntimeError("StemPrefill needs device tensors; there is no CPU path")
         assert q.dtype == k.dtype == v.dtype == torch.bfloat16
         assert k.stride() == v.stride() and k.shape == v.shape
         self.q, self.k, self.v = q, k, v
-        self.shape = sb.Shape.from_tensors(q, k, block_size, cu_seqlens)
+        self.shape = sb.Shape.from_tensors(q, k, block_size, cu_seqlens, chunk)
         self.n_sink, self.n_local = int(n_sink), int(n_local)
         self.beta, self.route_scale = float(beta), float(route_scale)
         self.ad_stride = int(ad_stride)
@@ -36,7 +40,10 @@ class StemPrefill:
         dev = q.device
         Hq, T = q.shape[1], q.shape[0]
         self.budget = budget_host.to(dev)
-        self.workspace = torch.empty(sb.stem_workspace_bytes(self.shape, self.ad_stride), dtype=torch.uint8, device=dev)
+        need = sb.stem_workspace_bytes(self.shape, self.ad_stride)
+        if workspace is not None:
+            assert workspace.dtype == torch.uint8 and workspace.numel() >= need
+        self.workspace = workspace if workspace is not None else torch.empty(need, dtype=torch.uint8, device=dev)
         self.scores = torch.empty((Hq, self.rows, self.nbmax), dtype=torch.float32, device=dev)
         self.counts = torch.empty((Hq, self.rows), dtype=torch.int32, device=dev)
         self.indices = torch.empty((Hq, self.rows, self.kmax), dtype=torch.int32, device=dev)
@@ -69,12 +76,15 @@ class StemPrefill:
         return self.out
 
     def pooled(self):
-        """Views of the pooled workspace: q_bar [Hq,R,S,d], k_bar [Hkv,R,S,d], m_v [Hkv,R] (fp32)."""
+        """Views of the pooled workspace: q_bar [Hq,R,S,d], k_bar [Hkv,Rk,S,d], m_v [Hkv,Rk] (fp32);
+        Rk counts the blocks of all sequences."""
         S = self.ad_stride
         qo, ko, mo = sb.stem_workspace_layout(self.shape, S)
         Hq, Hkv, d, R = self.q.shape[1], self.k.shape[1], self.q.shape[2], self.rows
+        B, cu = self.shape.c.block_size, self.shape.cu_seqlens
+        Rk = sum(-(-(cu[s + 1] - cu[s]) // B) for s in range(len(cu) - 1))
         f = self.workspace
         q_bar = f[qo:qo + 4 * Hq * R * S * d].view(torch.float32).view(Hq, R, S, d)
-        k_bar = f[ko:ko + 4 * Hkv * R * S * d].view(torch.float32).view(Hkv, R, S, d)
-        m_v = f[mo:mo + 4 * Hkv * R].view(torch.float32).view(Hkv, R)
+        k_bar = f[ko:ko + 4 * Hkv * Rk * S * d].view(torch.float32).view(Hkv, Rk, S, d)
+        m_v = f[mo:mo + 4 * Hkv * Rk].view(torch.float32).view(Hkv, Rk)
         return q_bar, k_bar, m_v

@@ -8,6 +8,8 @@ from oracle import stem_oracle as so
 from paper_2603_06274_amd import binding as sb
 from paper_2603_06274_amd import workloads as wl
 
+from paper_2603_06274_amd.prefill import StemPrefill
+
 import parity_util as pu
 
 pytestmark = pytest.mark.gpu
@@ -111,6 +113,64 @@ def test_anti_diagonal_strides_estimate_and_select(name, ad_stride):
     fin = np.isfinite(scores)
     assert np.abs(scores[fin] - mean_scores[fin]).max() > 1e-3
     say("%s S=%d: score err %.3g" % (w.name, ad_stride, err))
+
+
+def test_chunked_prefill_gives_the_rows_of_the_one_piece_call():
+    """A prompt processed in three chunks against its growing KV, with one workspace kept between
+    the calls (each call pools only its own blocks): every chunk's scores, lists, outputs and lse
+    are bit-identical to the matching rows of the one-piece call, whose parity with the oracle is
+    then checked on the assembled output."""
+    w = wl.small("chunks_b128", seed=41, num_q_heads=4, num_kv_heads=2, seq_lens=(1536, 700),
+                 block_size=128, k_start=(6, 4), n_sink=1, n_local=2, outliers=(3, 2))
+    B, cu = w.block_size, list(w.cu_seqlens)
+    data = wl.generate(w)
+    qkv = pu.host_arrays(data)
+    full = pu.device_prefill(w, data)
+    full.run()
+    torch.cuda.synchronize()
+    dev = torch.device("cuda:0")
+    q, k, v = (data[x].to(dev) for x in "qkv")
+    calls = [([0, 0], [512, 256]), ([512, 256], [1024, 700]), ([1024, 700], [1536, 700])]
+    need = 0
+    for starts, ends in calls:
+        shape = sb.Shape.from_tensors(q, k, B, cu, (starts, ends))
+        need = max(need, sb.stem_workspace_bytes(shape, 1))
+    ws = torch.full((need,), 0xFF, dtype=torch.uint8, device=dev)     # NaN patterns where nothing was pooled
+    out = torch.zeros_like(full.out)
+    full_row0 = [0, -(-(cu[1] - cu[0]) // B)]
+    for starts, ends in calls:
+        say("chunk", starts, ends)
+        qc = torch.cat([q[cu[s] + starts[s]:cu[s] + ends[s]] for s in range(2)]).contiguous()
+        pf = StemPrefill(qc, k, v, cu, B, w.k_start_blocks, w.mu, w.k_min, w.n_sink, w.n_local, w.beta,
+                         w.route_scale, w.softmax_scale, want_lse=True, chunk=(starts, ends), workspace=ws)
+        pf.run()
+        torch.cuda.synchronize()
+        r = t = 0
+        for s in range(2):
+            first, rows = starts[s] // B, -(-ends[s] // B) - starts[s] // B if ends[s] > starts[s] else 0
+            fr = full_row0[s] + first
+            n_tok = ends[s] - starts[s]
+            nb = pf.nbmax
+            assert torch.equal(pf.scores[:, r:r + rows, :nb], full.scores[:, fr:fr + rows, :nb])
+            assert torch.isinf(full.scores[:, fr:fr + rows, nb:]).all()
+            assert torch.equal(pf.counts[:, r:r + rows], full.counts[:, fr:fr + rows])
+            kk = min(pf.kmax, full.kmax)
+            assert torch.equal(pf.indices[:, r:r + rows, :kk], full.indices[:, fr:fr + rows, :kk])
+            assert (pf.indices[:, r:r + rows, kk:] == -1).all() and (full.indices[:, fr:fr + rows, kk:] == -1).all()
+            lo = cu[s] + starts[s]
+            assert torch.equal(pf.out[t:t + n_tok], full.out[lo:lo + n_tok])
+            assert torch.equal(pf.lse[:, t:t + n_tok], full.lse[:, lo:lo + n_tok])
+            out[lo:lo + n_tok] = pf.out[t:t + n_tok]
+            r += rows
+            t += n_tok
+        assert r == pf.rows and t == qc.shape[0]
+    # and the assembled chunks against the oracle's one-piece result
+    scores = pu.oracle_estimate(w, qkv)[3]
+    _, counts, indices = pu.oracle_select(w, scores)
+    same = pu.check_lists(w, full.counts.cpu().numpy(), full.indices.cpu().numpy(), counts, indices, scores, say)
+    assert same.all()
+    o_out, _ = so.sparse_attention(*qkv, cu, B, counts, indices, w.softmax_scale)
+    pu.check_output(out, o_out, w.name)
 
 
 def test_select_is_bit_exact_on_shared_fp32_scores():

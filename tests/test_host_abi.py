@@ -36,8 +36,8 @@ def test_rows_and_workspace():
     for S in (1, 2, 4, 8, 16):
         q_off, k_off, m_off = sb.stem_workspace_layout(shape, S)
         total = sb.stem_workspace_bytes(shape, S)
-        assert q_off == 0 and k_off >= 4 * 12 * S * 128 * 4 and m_off >= k_off + 2 * 12 * S * 128 * 4
-        assert total >= m_off + 2 * 12 * 4 and k_off % 256 == 0 and m_off % 256 == 0
+        assert k_off == 0 and m_off >= 2 * 12 * S * 128 * 4 and q_off >= m_off + 2 * 12 * 4
+        assert total >= q_off + 4 * 12 * S * 128 * 4 and q_off % 256 == 0 and m_off % 256 == 0
     n = ctypes.c_size_t()
     L = sb.lib()
     for S, want in ((0, sb.STEM_ERR_INVALID_ARG), (-2, sb.STEM_ERR_INVALID_ARG), (3, sb.STEM_ERR_INVALID_ARG),
@@ -76,6 +76,38 @@ def test_budget_schedule_random_sweep():
         shape = make_shape([0, n * 64 - int(r.integers(0, 64))], B=64)
         got, _ = sb.stem_budget_schedule(shape, [ks], mu, k_min, n_sink, n_local)
         assert got.numpy().tolist() == so.tpd_budget(n, ks, mu, k_min, n_sink, n_local).tolist()
+
+
+def test_chunked_shapes_rows_and_schedule():
+    """A chunked call covers some query blocks of each sequence; rows keep their index in the
+    sequence, so its budget is the matching slice of the whole-sequence schedule."""
+    cu, B = [0, 1536, 2236], 128
+    whole = make_shape(cu, B=B)
+    assert sb.stem_rows(whole) == (12 + 6, 12)
+    chunk = sb.Shape(4, 2, 128, B, cu, (4 * 128, 128), (2 * 128, 128), chunk=([512, 256], [1024, 700]))
+    assert sb.stem_rows(chunk) == (4 + 4, 8)
+    tail = sb.Shape(4, 2, 128, B, cu, (4 * 128, 128), (2 * 128, 128), chunk=([1024, 700], [1536, 700]))
+    assert sb.stem_rows(tail) == (4, 12)
+    ks, mu, k_min, n_sink, n_local = [7.5, 4], 0.7, 3, 1, 2
+    full, _ = sb.stem_budget_schedule(whole, ks, mu, k_min, n_sink, n_local)
+    want = so.packed_budget(cu, B, ks, mu, k_min, n_sink, n_local)
+    assert full.numpy().tolist() == want.tolist()
+    got, kmax = sb.stem_budget_schedule(chunk, ks, mu, k_min, n_sink, n_local)
+    assert got.numpy().tolist() == want[4:8].tolist() + want[12 + 2:12 + 6].tolist()
+    assert kmax == max(got.numpy().tolist())
+    got, _ = sb.stem_budget_schedule(tail, ks, mu, k_min, n_sink, n_local)
+    assert got.numpy().tolist() == want[8:12].tolist()
+    # the key parts of the workspace do not move with the chunk
+    assert sb.stem_workspace_layout(chunk, 2)[1:] == sb.stem_workspace_layout(whole, 2)[1:]
+    n = ctypes.c_size_t()
+    L = sb.lib()
+    for starts, ends in (([100, 0], [1024, 700]), ([0, 0], [1000, 700]), ([512, 256], [256, 700]),
+                         ([0, 0], [1536, 800]), ([-128, 0], [1536, 700])):
+        bad = sb.Shape(4, 2, 128, B, cu, (4 * 128, 128), (2 * 128, 128), chunk=(starts, ends))
+        assert L.stem_workspace_bytes(bad.ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG, (starts, ends)
+    half = sb.Shape(4, 2, 128, B, cu, (4 * 128, 128), (2 * 128, 128), chunk=([0, 0], [1536, 700]))
+    half.c.host_chunk_end = ctypes.POINTER(ctypes.c_int32)()
+    assert L.stem_workspace_bytes(half.ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
 
 
 def test_bad_arguments_are_rejected_on_the_host():
