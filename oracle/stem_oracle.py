@@ -11,6 +11,8 @@ What each function follows:
   tpd_budget         Eq. 3 (Token Position-Decay) in block units, Algorithm 1 step 3b, plus the
                      forced initial/local windows and minimum budget of Implementation Details
   select_blocks      Algorithm 1, step 3c (Top-k(i) of the metric row)
+  group_scores       extension for grouped-query attention: the metric reduced over the query
+                     heads of a KV head, so that one list serves the whole group
   sparse_attention   Algorithm 1, step 3d (exact softmax attention over the gathered blocks), with
                      the causal constraint j <= i of the Token Position-Decay analysis
 
@@ -215,6 +217,27 @@ def select_blocks(scores: np.ndarray, budget: np.ndarray, cu_seqlens: Sequence[i
             counts[h, r] = len(c)
             indices[h, r, :len(c)] = c
     return counts, indices
+
+
+def group_scores(scores: np.ndarray, num_kv_heads: int, reduce: str = "max") -> np.ndarray:
+    """Group-shared selection for grouped-query attention (an extension: the paper derives the
+    method per head and names group sharing only for a comparison system in Related Work).
+
+    scores [Hq,R,NB] -> [Hkv,R,NB]: the metric of KV head g for a block pair is the maximum
+    ("max") or the mean ("mean") of the metric of its G = Hq/Hkv query heads h = g*G .. g*G+G-1.
+    One list per (KV head, row) is then selected from it and used by all G heads.  Entries that
+    are -inf (non-causal) for one head are -inf for all, and stay -inf.
+    """
+    Hq, R, NB = scores.shape
+    G = Hq // num_kv_heads
+    if G * num_kv_heads != Hq:
+        raise ValueError("Hq must be a multiple of Hkv")
+    grouped = scores.reshape(num_kv_heads, G, R, NB)
+    if reduce == "max":
+        return grouped.max(axis=1)
+    if reduce == "mean":
+        return grouped.sum(axis=1) / G
+    raise ValueError("reduce must be 'max' or 'mean'")
 
 
 # ------------------------------------------------------------------------------------------------

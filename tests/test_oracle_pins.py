@@ -333,6 +333,38 @@ def full_budget_lists(cu, B, Hq):
     return counts, idx
 
 
+def test_group_scores_brute_force_and_invariants():
+    """The group reduction written out with loops; G = 1 is the identity; reordering the heads of
+    a group changes nothing; max >= mean; the shared list is the per-head list when the heads of a
+    group carry equal scores."""
+    r = np.random.default_rng(11)
+    Hq, Hkv, R, NB = 6, 2, 5, 5
+    G = Hq // Hkv
+    sc = r.normal(size=(Hq, R, NB))
+    sc[:, np.triu_indices(R, 1)[0], np.triu_indices(R, 1)[1]] = -np.inf
+    for how in ("max", "mean"):
+        got = so.group_scores(sc, Hkv, how)
+        assert got.shape == (Hkv, R, NB)
+        for g in range(Hkv):
+            for i in range(R):
+                for j in range(NB):
+                    vals = [sc[g * G + x, i, j] for x in range(G)]
+                    want = max(vals) if how == "max" else sum(vals) / G
+                    assert got[g, i, j] == want or abs(got[g, i, j] - want) < 1e-15
+        assert np.array_equal(so.group_scores(sc, Hq, how), sc)
+        perm = np.concatenate([r.permutation(G), G + r.permutation(G)])
+        assert np.allclose(so.group_scores(sc[perm], Hkv, how), got, atol=1e-15)
+    fin = np.isfinite(sc[0])
+    assert (so.group_scores(sc, Hkv, "max")[:, fin] >= so.group_scores(sc, Hkv, "mean")[:, fin]).all()
+    same = np.repeat(sc[::G], G, axis=0)                     # every head of a group equal to its first
+    budget = np.array([1, 2, 2, 3, 3], dtype=np.int32)
+    c1, i1 = so.select_blocks(same, budget, [0, R * 4], 4, 1, 1)
+    c2, i2 = so.select_blocks(so.group_scores(same, Hkv, "max"), budget, [0, R * 4], 4, 1, 1)
+    assert np.array_equal(c1[::G], c2) and np.array_equal(i1[::G], i2)
+    with pytest.raises(ValueError):
+        so.group_scores(sc, 4, "max")
+
+
 def test_full_budget_equals_dense_causal_attention():
     # catches: missing intra-block causal mask, wrong GQA map, cross-sequence leakage, missing scale,
     # softmax over the wrong axis; ragged tails included
