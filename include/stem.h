@@ -150,23 +150,41 @@ int stem_estimate(const stem_shape* shape, const void* q, const void* k, const v
                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Group-shared selection for grouped-query attention (an extension: the paper derives the method
+ * per head).  Reduces the metric over the G = Hq / Hkv query heads of each KV head:
+ *   group_scores[g, r, j] = max (STEM_GROUP_MAX) or mean (STEM_GROUP_MEAN) over h in g*G .. g*G+G-1
+ *                           of scores[h, r, j]                 (-inf stays -inf)
+ * scores is fp32 [Hq, R, NBmax], group_scores fp32 [Hkv, R, NBmax].  Selecting from group_scores
+ * with lists_per_kv_head = 1 gives one list per (KV head, row), which stem_sparse_attn then uses
+ * for all G heads of the group: G times fewer lists, and the heads of a group read the same K/V
+ * blocks at the same time.
+ */
+#define STEM_GROUP_MAX   0
+#define STEM_GROUP_MEAN  1
+int stem_group_scores(const stem_shape* shape, const float* scores, int32_t reduce,
+                      float* group_scores, void* hip_stream);
+
+/*
  * Stage 2, Algorithm 1 step 3c with forced windows.  For every head h and row r (local index i):
  *   k = min(i + 1, max(budget[r], |forced(i)|));
  *   list = forced(i) united with the k - |forced(i)| best-scoring other causal blocks, equal
  *          scores going to the lower block index; written ascending.
  * budget is device int32 [R] (from stem_budget_schedule, copied by the caller).
  * counts is device int32 [Hq, R]; indices is device int32 [Hq, R, kmax], padded with -1.
+ * With lists_per_kv_head = 1 "head" means KV head: scores is [Hkv, R, NBmax] (from
+ * stem_group_scores), counts [Hkv, R], indices [Hkv, R, kmax]; 0 is the paper's per-head selection.
  * kmax is the row pitch of indices.  It must be at least n_sink + n_local (or at least NBmax), so the
  * forced blocks always fit; a row whose budget exceeds kmax is cut to kmax blocks (k = min(k, kmax)).
  */
 int stem_select(const stem_shape* shape, const float* scores, const int32_t* budget,
-                int32_t n_sink, int32_t n_local, int32_t* counts, int32_t* indices, int32_t kmax,
-                void* hip_stream);
+                int32_t n_sink, int32_t n_local, int32_t lists_per_kv_head, int32_t* counts,
+                int32_t* indices, int32_t kmax, void* hip_stream);
 
 /*
  * Stage 3, Algorithm 1 step 3d: for every head h, row r and valid query token t of the row's block
  *   out[t, h, :] = sum_u softmax_u( softmax_scale * <Q[t,h], K[u,g]> ) V[u,g]
- * over the tokens u <= t of the key blocks indices[h, r, 0 .. counts[h,r]).  bf16 inputs, bf16 MFMA
+ * over the tokens u <= t of the key blocks indices[h, r, 0 .. counts[h,r]) (of indices[h / G, r, ..]
+ * with counts [Hkv, R] and indices [Hkv, R, kmax] if lists_per_kv_head = 1).  bf16 inputs, bf16 MFMA
  * products with fp32 accumulation, fp32 softmax, bf16 output with Q's strides.  softmax_scale > 0.
  * lse (device fp32 [Hq, T], may be NULL) receives log sum_u exp(softmax_scale * <Q,K>) per query.
  * Any list is accepted, not only stem_select's, provided each row's list is ascending, causal
@@ -177,7 +195,8 @@ int stem_select(const stem_shape* shape, const float* scores, const int32_t* bud
  */
 int stem_sparse_attn(const stem_shape* shape, const void* q, const void* k, const void* v,
                      const int32_t* counts, const int32_t* indices, int32_t kmax,
-                     float softmax_scale, void* out, float* lse, void* hip_stream);
+                     int32_t lists_per_kv_head, float softmax_scale, void* out, float* lse,
+                     void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -68,8 +68,9 @@ def lib() -> ctypes.CDLL:
             "stem_pool": [shp, vp, vp, vp, i32, vp, sz, vp],
             "stem_block_scores": [shp, vp, sz, i32, f32, f32, vp, vp],
             "stem_estimate": [shp, vp, vp, vp, f32, f32, i32, vp, vp, sz, vp],
-            "stem_select": [shp, vp, vp, i32, i32, vp, vp, i32, vp],
-            "stem_sparse_attn": [shp, vp, vp, vp, vp, vp, i32, f32, vp, vp, vp],
+            "stem_group_scores": [shp, vp, i32, vp, vp],
+            "stem_select": [shp, vp, vp, i32, i32, i32, vp, vp, i32, vp],
+            "stem_sparse_attn": [shp, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp, vp],
         }
         for name, args in sigs.items():
             fn = getattr(L, name)
@@ -81,6 +82,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTED = ["stem_version", "stem_strerror", "stem_rows", "stem_workspace_bytes",
             "stem_workspace_layout", "stem_budget_schedule", "stem_pool", "stem_block_scores",
+            "stem_group_scores",
             "stem_estimate", "stem_select", "stem_sparse_attn"]
 
 
@@ -192,14 +194,25 @@ def stem_estimate(shape: Shape, q, k, v, beta: float, route_scale: float, ad_str
                                workspace.numel() * workspace.element_size(), _stream()), "stem_estimate")
 
 
+STEM_GROUP_MAX, STEM_GROUP_MEAN = 0, 1
+
+
+def stem_group_scores(shape: Shape, scores: torch.Tensor, reduce: int, group_scores: torch.Tensor) -> None:
+    _check(lib().stem_group_scores(shape.ref(), _ptr(scores), int(reduce), _ptr(group_scores), _stream()),
+           "stem_group_scores")
+
+
 def stem_select(shape: Shape, scores: torch.Tensor, budget: torch.Tensor, n_sink: int, n_local: int,
-                counts: torch.Tensor, indices: torch.Tensor, kmax: int) -> None:
+                counts: torch.Tensor, indices: torch.Tensor, kmax: int,
+                lists_per_kv_head: bool = False) -> None:
     _check(lib().stem_select(shape.ref(), _ptr(scores), _ptr(budget), int(n_sink), int(n_local),
-                             _ptr(counts), _ptr(indices), int(kmax), _stream()), "stem_select")
+                             int(bool(lists_per_kv_head)), _ptr(counts), _ptr(indices), int(kmax), _stream()),
+           "stem_select")
 
 
 def stem_sparse_attn(shape: Shape, q, k, v, counts: torch.Tensor, indices: torch.Tensor, kmax: int,
-                     softmax_scale: float, out: torch.Tensor, lse: Optional[torch.Tensor]) -> None:
+                     softmax_scale: float, out: torch.Tensor, lse: Optional[torch.Tensor],
+                     lists_per_kv_head: bool = False) -> None:
     _check(lib().stem_sparse_attn(shape.ref(), _ptr(q), _ptr(k), _ptr(v), _ptr(counts), _ptr(indices),
-                                  int(kmax), float(softmax_scale), _ptr(out), _ptr(lse), _stream()),
-           "stem_sparse_attn")
+                                  int(kmax), int(bool(lists_per_kv_head)), float(softmax_scale), _ptr(out),
+                                  _ptr(lse), _stream()), "stem_sparse_attn")

@@ -246,31 +246,46 @@ int stem_estimate(const stem_shape* shape, const void* q, const void* k, const v
                              hip_stream);
 }
 
-int stem_select(const stem_shape* shape, const float* scores, const int32_t* budget, int32_t n_sink,
-                int32_t n_local, int32_t* counts, int32_t* indices, int32_t kmax, void* hip_stream) {
+int stem_group_scores(const stem_shape* shape, const float* scores, int32_t reduce,
+                      float* group_scores, void* hip_stream) {
     Problem p;
     int st = make_problem(shape, &p);
     if (st != STEM_OK) return st;
+    if (!scores || !group_scores) return STEM_ERR_INVALID_ARG;
+    if (reduce != STEM_GROUP_MAX && reduce != STEM_GROUP_MEAN) return STEM_ERR_INVALID_ARG;
+    if (p.R == 0) return STEM_OK;
+    return launch_group_scores(p, scores, reduce, group_scores, static_cast<hipStream_t>(hip_stream));
+}
+
+int stem_select(const stem_shape* shape, const float* scores, const int32_t* budget, int32_t n_sink,
+                int32_t n_local, int32_t lists_per_kv_head, int32_t* counts, int32_t* indices,
+                int32_t kmax, void* hip_stream) {
+    Problem p;
+    int st = make_problem(shape, &p);
+    if (st != STEM_OK) return st;
+    if (lists_per_kv_head != 0 && lists_per_kv_head != 1) return STEM_ERR_INVALID_ARG;
     if (!scores || !budget || !counts || !indices) return STEM_ERR_INVALID_ARG;
     if (n_sink < 0 || n_local < 0 || kmax < 1) return STEM_ERR_INVALID_ARG;
     if ((int64_t)kmax < (int64_t)n_sink + n_local && kmax < p.NBmax) return STEM_ERR_INVALID_ARG;
     if (p.R == 0) return STEM_OK;
-    return launch_select(p, scores, budget, n_sink, n_local, counts, indices, kmax,
-                         static_cast<hipStream_t>(hip_stream));
+    return launch_select(p, lists_per_kv_head ? p.Hkv : p.Hq, scores, budget, n_sink, n_local, counts,
+                         indices, kmax, static_cast<hipStream_t>(hip_stream));
 }
 
 int stem_sparse_attn(const stem_shape* shape, const void* q, const void* k, const void* v,
                      const int32_t* counts, const int32_t* indices, int32_t kmax,
-                     float softmax_scale, void* out, float* lse, void* hip_stream) {
+                     int32_t lists_per_kv_head, float softmax_scale, void* out, float* lse,
+                     void* hip_stream) {
     Problem p;
     int st = make_problem(shape, &p);
     if (st != STEM_OK) return st;
+    if (lists_per_kv_head != 0 && lists_per_kv_head != 1) return STEM_ERR_INVALID_ARG;
     if ((st = check_qkv(q, k, v)) != STEM_OK) return st;
     if (!counts || !indices || !out || !aligned16(out) || kmax < 1) return STEM_ERR_INVALID_ARG;
     if (!std::isfinite(softmax_scale) || !(softmax_scale > 0.f)) return STEM_ERR_INVALID_ARG;
     if (p.R == 0) return STEM_OK;
-    return launch_sparse_attn(p, q, k, v, counts, indices, kmax, softmax_scale, out, lse,
-                              static_cast<hipStream_t>(hip_stream));
+    return launch_sparse_attn(p, q, k, v, counts, indices, kmax, lists_per_kv_head != 0, softmax_scale,
+                              out, lse, static_cast<hipStream_t>(hip_stream));
 }
 
 }  // extern "C"

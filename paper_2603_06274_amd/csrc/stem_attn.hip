@@ -119,8 +119,8 @@ __device__ __forceinline__ void sparse_attn_body(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ counts, const int32_t* __restrict__ indices,
     uint16_t* __restrict__ out, float* __restrict__ lse, const SeqTable& seq, int Hq, int R, int G,
-    int T, int kmax, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh, float scale,
-    int items_per_xcd, unsigned char* __restrict__ k_lds, unsigned char* __restrict__ v_lds) {
+    int T, int kmax, bool shared_lists, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh,
+    float scale, int items_per_xcd, unsigned char* __restrict__ k_lds, unsigned char* __restrict__ v_lds) {
     constexpr int KT = B / 32;                         // 32-key tiles per block
 
     // ---- which (head, row): consecutive workgroup ids go to different XCDs, so give every XCD a
@@ -147,8 +147,9 @@ __device__ __forceinline__ void sparse_attn_body(
     const int tok_q = tok_q0 + qrow;
     const bool q_valid = tok_q < q_hi;
 
-    const int cnt = min(counts[(int64_t)h * R + r], kmax);
-    const int32_t* list = indices + ((int64_t)h * R + r) * kmax;
+    const int lh = shared_lists ? g : h;               // whose list: the KV head's or the query head's
+    const int cnt = min(counts[(int64_t)lh * R + r], kmax);
+    const int32_t* list = indices + ((int64_t)lh * R + r) * kmax;
     const uint16_t* k_head = k + (int64_t)g * kv_sh;
     const uint16_t* v_head = v + (int64_t)g * kv_sh;
 
@@ -453,17 +454,18 @@ __global__ __launch_bounds__(B * 2, 2) void sparse_attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ counts, const int32_t* __restrict__ indices,
     uint16_t* __restrict__ out, float* __restrict__ lse, SeqTable seq, int Hq, int R, int G, int T,
-    int kmax, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh, float scale,
+    int kmax, bool shared_lists, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh, float scale,
     int items_per_xcd) {
     __shared__ __attribute__((aligned(1024))) unsigned char k_lds[B * kRowBytes];
     __shared__ __attribute__((aligned(1024))) unsigned char v_lds[B * kRowBytes];
-    sparse_attn_body<B>(q, k, v, counts, indices, out, lse, seq, Hq, R, G, T, kmax, q_st, q_sh, kv_st,
-                        kv_sh, scale, items_per_xcd, k_lds, v_lds);
+    sparse_attn_body<B>(q, k, v, counts, indices, out, lse, seq, Hq, R, G, T, kmax, shared_lists, q_st, q_sh,
+                        kv_st, kv_sh, scale, items_per_xcd, k_lds, v_lds);
 }
 
 int launch_sparse_attn(const Problem& p, const void* q, const void* k, const void* v,
                        const int32_t* counts, const int32_t* indices, int32_t kmax,
-                       float softmax_scale, void* out, float* lse, hipStream_t stream) {
+                       bool lists_per_kv_head, float softmax_scale, void* out, float* lse,
+                       hipStream_t stream) {
     // the block requests address one sequence of one KV head through a 32-bit byte offset, with
     // offsets from 2^31 on reserved for requests that must fetch nothing
     for (int s = 0; s < p.batch; ++s) {
@@ -480,11 +482,11 @@ int launch_sparse_attn(const Problem& p, const void* q, const void* k, const voi
     uint16_t* oo = static_cast<uint16_t*>(out);
     if (p.B == 128)
         hipLaunchKernelGGL(sparse_attn_kernel<128>, grid, dim3(256), 0, stream, qq, kk, vv, counts,
-                           indices, oo, lse, p.seq, p.Hq, p.R, p.G, p.T, kmax, p.q_st, p.q_sh,
+                           indices, oo, lse, p.seq, p.Hq, p.R, p.G, p.T, kmax, lists_per_kv_head, p.q_st, p.q_sh,
                            p.kv_st, p.kv_sh, softmax_scale, (int)per_xcd);
     else
         hipLaunchKernelGGL(sparse_attn_kernel<64>, grid, dim3(128), 0, stream, qq, kk, vv, counts,
-                           indices, oo, lse, p.seq, p.Hq, p.R, p.G, p.T, kmax, p.q_st, p.q_sh,
+                           indices, oo, lse, p.seq, p.Hq, p.R, p.G, p.T, kmax, lists_per_kv_head, p.q_st, p.q_sh,
                            p.kv_st, p.kv_sh, softmax_scale, (int)per_xcd);
     return check_launch();
 }

@@ -49,12 +49,16 @@ int launch_pool(const Problem& p, int ad_stride, const void* q, const void* k, c
 int launch_block_scores(const Problem& p, int ad_stride, const float* q_bar, const float* k_bar,
                         const float* m_v, float beta, float route_scale, float* scores,
                         hipStream_t stream);
-int launch_select(const Problem& p, const float* scores, const int32_t* budget, int32_t n_sink,
-                  int32_t n_local, int32_t* counts, int32_t* indices, int32_t kmax,
+int launch_group_scores(const Problem& p, const float* scores, int reduce, float* group_scores,
+                        hipStream_t stream);
+// heads = number of lists per row: Hq, or Hkv for group-shared lists
+int launch_select(const Problem& p, int heads, const float* scores, const int32_t* budget,
+                  int32_t n_sink, int32_t n_local, int32_t* counts, int32_t* indices, int32_t kmax,
                   hipStream_t stream);
 int launch_sparse_attn(const Problem& p, const void* q, const void* k, const void* v,
                        const int32_t* counts, const int32_t* indices, int32_t kmax,
-                       float softmax_scale, void* out, float* lse, hipStream_t stream);
+                       bool lists_per_kv_head, float softmax_scale, void* out, float* lse,
+                       hipStream_t stream);
 
 inline int check_launch() {
     return hipGetLastError() == hipSuccess ? STEM_OK : STEM_ERR_HIP;

@@ -134,4 +134,64 @@ int launch_block_scores(const Problem& p, int ad_stride, const float* q_bar, con
     return check_launch();
 }
 
+__global__ __launch_bounds__(256) void group_scores_scalar_kernel(const float* __restrict__ scores,
+                                                                  float* __restrict__ group_scores,
+                                                                  int64_t per_head, int G, int take_mean,
+                                                                  int64_t total) {
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int64_t g = idx / per_head, off = idx - g * per_head;
+    const float* src = scores + g * G * per_head + off;
+    float acc = src[0];
+    for (int x = 1; x < G; ++x) {
+        const float y = src[(int64_t)x * per_head];
+        acc = take_mean ? acc + y : fmaxf(acc, y);
+    }
+    group_scores[idx] = take_mean ? acc / (float)G : acc;
+}
+
+// Group-shared selection for grouped-query attention: the metric of a KV head is the maximum or
+// the mean of the metric of its G query heads.  One thread per four consecutive key blocks; the G
+// values are combined in head order (deterministic fp32).
+__global__ __launch_bounds__(256) void group_scores_kernel(const float* __restrict__ scores,
+                                                           float* __restrict__ group_scores,
+                                                           int64_t per_head, int G, int take_mean,
+                                                           int64_t total) {
+    const int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;   // per_head % 4 == 0 or scalar tail
+    if (idx >= total) return;
+    const int64_t g = idx / per_head, off = idx - g * per_head;
+    const float* src = scores + g * G * per_head + off;
+    const int n = (int)min((int64_t)4, per_head - off);
+    float acc[4];
+    for (int e = 0; e < n; ++e) acc[e] = src[e];
+    for (int x = 1; x < G; ++x)
+        for (int e = 0; e < n; ++e) {
+            const float y = src[(int64_t)x * per_head + e];
+            acc[e] = take_mean ? acc[e] + y : fmaxf(acc[e], y);
+        }
+    for (int e = 0; e < n; ++e) group_scores[idx + e] = take_mean ? acc[e] / (float)G : acc[e];
+}
+
+int launch_group_scores(const Problem& p, const float* scores, int reduce, float* group_scores,
+                        hipStream_t stream) {
+    const int64_t per_head = (int64_t)p.R * p.NBmax;
+    const int64_t total = per_head * p.Hkv;
+    if (total == 0) return STEM_OK;
+    // a thread's four elements must not straddle two heads
+    if (per_head % 4) {
+        // rare shapes: fall back to one element per thread by widening the index space
+        const int64_t threads = total;
+        const int64_t blocks = (threads + 255) / 256;
+        if (blocks > 0x7fffffff) return STEM_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(group_scores_scalar_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, scores,
+                           group_scores, per_head, p.G, reduce == STEM_GROUP_MEAN, total);
+        return check_launch();
+    }
+    const int64_t blocks = (total / 4 + 255) / 256;
+    if (blocks > 0x7fffffff) return STEM_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(group_scores_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, scores, group_scores,
+                       per_head, p.G, reduce == STEM_GROUP_MEAN, total);
+    return check_launch();
+}
+
 }  // namespace stem

@@ -95,16 +95,16 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     if (lane == 0) counts[(int64_t)h * R + r] = k;
 }
 
-int launch_select(const Problem& p, const float* scores, const int32_t* budget, int32_t n_sink,
-                  int32_t n_local, int32_t* counts, int32_t* indices, int32_t kmax,
+int launch_select(const Problem& p, int heads, const float* scores, const int32_t* budget,
+                  int32_t n_sink, int32_t n_local, int32_t* counts, int32_t* indices, int32_t kmax,
                   hipStream_t stream) {
-    const int64_t items = (int64_t)p.Hq * p.R;
+    const int64_t items = (int64_t)heads * p.R;
     const int64_t blocks = (items + kSelectThreads / 64 - 1) / (kSelectThreads / 64);
     if (blocks > 0x7fffffff) return STEM_ERR_UNSUPPORTED;
     dim3 grid((unsigned)blocks), block(kSelectThreads);
 #define STEM_SELECT_LAUNCH(N)                                                                      \
     hipLaunchKernelGGL(select_kernel<N>, grid, block, 0, stream, scores, budget, counts, indices,  \
-                       p.seq, p.Hq, p.R, p.NBmax, n_sink, n_local, kmax)
+                       p.seq, heads, p.R, p.NBmax, n_sink, n_local, kmax)
     if (p.NBmax <= 64 * 4) STEM_SELECT_LAUNCH(4);
     else if (p.NBmax <= 64 * 16) STEM_SELECT_LAUNCH(16);
     else if (p.NBmax <= 64 * 64) STEM_SELECT_LAUNCH(64);

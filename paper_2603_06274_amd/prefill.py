@@ -22,7 +22,7 @@ class StemPrefill:
                  block_size: int, k_start_blocks: Sequence[float], mu: float = 0.7, k_min: int = 0,
                  n_sink: int = 4, n_local: int = 4, beta: float = 0.2, route_scale: float = 1.0,
                  softmax_scale: Optional[float] = None, want_lse: bool = False, ad_stride: int = 1,
-                 chunk=None, workspace: Optional[torch.Tensor] = None):
+                 chunk=None, workspace: Optional[torch.Tensor] = None, group_share: Optional[str] = None):
         if not (q.is_cuda and k.is_cuda and v.is_cuda):
             raise RuntimeError("StemPrefill needs device tensors; there is no CPU path")
         assert q.dtype == k.dtype == v.dtype == torch.bfloat16
@@ -32,6 +32,9 @@ class StemPrefill:
         self.n_sink, self.n_local = int(n_sink), int(n_local)
         self.beta, self.route_scale = float(beta), float(route_scale)
         self.ad_stride = int(ad_stride)
+        # group_share "max" / "mean": one list per (KV head, row) from the group-reduced metric
+        assert group_share in (None, "max", "mean")
+        self.group_share = group_share
         self.softmax_scale = float(softmax_scale if softmax_scale is not None else q.shape[2] ** -0.5)
         self.rows, self.nbmax = sb.stem_rows(self.shape)
         budget_host, kmax = sb.stem_budget_schedule(self.shape, k_start_blocks, mu, k_min, n_sink, n_local)
@@ -45,8 +48,11 @@ class StemPrefill:
             assert workspace.dtype == torch.uint8 and workspace.numel() >= need
         self.workspace = workspace if workspace is not None else torch.empty(need, dtype=torch.uint8, device=dev)
         self.scores = torch.empty((Hq, self.rows, self.nbmax), dtype=torch.float32, device=dev)
-        self.counts = torch.empty((Hq, self.rows), dtype=torch.int32, device=dev)
-        self.indices = torch.empty((Hq, self.rows, self.kmax), dtype=torch.int32, device=dev)
+        Hl = k.shape[1] if group_share else Hq         # lists per row
+        self.group_scores = (torch.empty((Hl, self.rows, self.nbmax), dtype=torch.float32, device=dev)
+                             if group_share else None)
+        self.counts = torch.empty((Hl, self.rows), dtype=torch.int32, device=dev)
+        self.indices = torch.empty((Hl, self.rows, self.kmax), dtype=torch.int32, device=dev)
         self.out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=dev)  # O uses Q's strides
         self.lse = torch.empty((Hq, T), dtype=torch.float32, device=dev) if want_lse else None
 
@@ -62,12 +68,17 @@ class StemPrefill:
                              self.scores)
 
     def select(self) -> None:
-        sb.stem_select(self.shape, self.scores, self.budget, self.n_sink, self.n_local, self.counts,
-                       self.indices, self.kmax)
+        if self.group_share:
+            sb.stem_group_scores(self.shape, self.scores,
+                                 sb.STEM_GROUP_MAX if self.group_share == "max" else sb.STEM_GROUP_MEAN,
+                                 self.group_scores)
+        sb.stem_select(self.shape, self.group_scores if self.group_share else self.scores, self.budget,
+                       self.n_sink, self.n_local, self.counts, self.indices, self.kmax,
+                       lists_per_kv_head=bool(self.group_share))
 
     def attend(self) -> None:
         sb.stem_sparse_attn(self.shape, self.q, self.k, self.v, self.counts, self.indices, self.kmax,
-                            self.softmax_scale, self.out, self.lse)
+                            self.softmax_scale, self.out, self.lse, lists_per_kv_head=bool(self.group_share))
 
     def run(self) -> torch.Tensor:
         self.estimate()

@@ -173,6 +173,46 @@ def test_chunked_prefill_gives_the_rows_of_the_one_piece_call():
     pu.check_output(out, o_out, w.name)
 
 
+@pytest.mark.parametrize("how", ["max", "mean"])
+@pytest.mark.parametrize("name", ["packed_b128", "ragged_b64"])
+def test_group_shared_selection(name, how):
+    """One list per (KV head, row) from the group-reduced metric, used by all heads of the group."""
+    w = SMALL[name]
+    G = w.num_q_heads // w.num_kv_heads
+    say("case", w.name, "seed", w.seed, "group", how, "G", G)
+    data = wl.generate(w)
+    qkv = pu.host_arrays(data)
+    dev = torch.device("cuda:0")
+    q, k, v = (data[x].to(dev) for x in "qkv")
+    pf = StemPrefill(q, k, v, w.cu_seqlens, w.block_size, w.k_start_blocks, w.mu, w.k_min, w.n_sink,
+                     w.n_local, w.beta, w.route_scale, w.softmax_scale, want_lse=True, group_share=how)
+    pf.run()
+    torch.cuda.synchronize()
+    scores = pu.oracle_estimate(w, qkv)[3]
+    grouped = so.group_scores(scores, w.num_kv_heads, how)
+    assert pf.counts.shape[0] == w.num_kv_heads
+    pu.check_scores(pf.group_scores.cpu().numpy(), grouped)
+    _, counts, indices = pu.oracle_select(w, grouped)
+    same = pu.check_lists(w, pf.counts.cpu().numpy(), pf.indices.cpu().numpy(), counts, indices, grouped, say)
+    # every query head attends over its KV head's list
+    o_out, o_lse = so.sparse_attention(*qkv, w.cu_seqlens, w.block_size, np.repeat(counts, G, axis=0),
+                                       np.repeat(indices, G, axis=0), w.softmax_scale)
+    B = w.block_size
+    for (lo, hi, nb, row0) in so.sequence_table(w.cu_seqlens, B):
+        for i in range(nb):
+            for h in range(w.num_q_heads):
+                if not same[h // G, row0 + i]:
+                    o_out[lo + i * B:min(lo + (i + 1) * B, hi), h] = np.nan
+                    o_lse[h, lo + i * B:min(lo + (i + 1) * B, hi)] = np.nan
+    pu.check_output(pf.out, o_out, w.name)
+    m = ~np.isnan(o_lse)
+    assert np.abs(pf.lse.cpu().numpy()[m] - o_lse[m]).max() <= 5e-3
+    # the shared lists differ from the per-head ones (the reduction does something)
+    _, c_h, i_h = pu.oracle_select(w, scores)
+    assert not np.array_equal(np.repeat(indices, G, axis=0)[:, :, :min(indices.shape[2], i_h.shape[2])],
+                              i_h[:, :, :min(indices.shape[2], i_h.shape[2])])
+
+
 def test_select_is_bit_exact_on_shared_fp32_scores():
     """Stage 2 alone, on one fp32 score tensor given to both sides (exactly representable in fp64, so
     no near-tie allowance), with planted exact ties, +-0, and equal rows."""

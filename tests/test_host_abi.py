@@ -136,19 +136,22 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.stem_estimate(good.ref(), 0x1000, 0x1000, 0x1000, 0.2, 1.0, 32, 0x1000, 0x1000, 1 << 30, None) == sb.STEM_ERR_UNSUPPORTED
     assert L.stem_estimate(good.ref(), 0x1000, 0x1000, 0x1000, 0.2, 1.0, 0, 0x1000, 0x1000, 1 << 30, None) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_block_scores(good.ref(), 0x1000, 1 << 30, 1, float("nan"), 1.0, 0x1000, None) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_select(good.ref(), 0x1000, 0x1000, 1, 1, 0x1000, None, 8, None) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_select(good.ref(), 0x1000, 0x1000, -1, 1, 0x1000, 0x1000, 8, None) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_select(good.ref(), 0x1000, 0x1000, 3, 3, 0x1000, 0x1000, 4, None) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_sparse_attn(good.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0, 0.1, 0x1000, None, None) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_sparse_attn(good.ref(), 0x1000, 0x1000, 0x1000, None, 0x1000, 4, 0.1, 0x1000, None, None) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_sparse_attn(good.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 4, -1.0, 0x1000, None, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_select(good.ref(), 0x1000, 0x1000, 1, 1, 0, 0x1000, None, 8, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_select(good.ref(), 0x1000, 0x1000, -1, 1, 0, 0x1000, 0x1000, 8, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_select(good.ref(), 0x1000, 0x1000, 3, 3, 0, 0x1000, 0x1000, 4, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_select(good.ref(), 0x1000, 0x1000, 1, 1, 2, 0x1000, 0x1000, 8, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_group_scores(good.ref(), 0x1000, 7, 0x1000, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_group_scores(good.ref(), None, 0, 0x1000, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_sparse_attn(good.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0, 0, 0.1, 0x1000, None, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_sparse_attn(good.ref(), 0x1000, 0x1000, 0x1000, None, 0x1000, 4, 0, 0.1, 0x1000, None, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_sparse_attn(good.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 4, 0, -1.0, 0x1000, None, None) == sb.STEM_ERR_INVALID_ARG
     # one sequence of one KV head must stay below 2 GiB for the attention kernel's block addressing
     wide = sb.Shape(4, 2, 128, 64, [0, 4096], (4 * 128, 128), (1 << 19, 128))
-    assert L.stem_sparse_attn(wide.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 4, 0.1, 0x1000, None, None) == sb.STEM_ERR_UNSUPPORTED
+    assert L.stem_sparse_attn(wide.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 4, 0, 0.1, 0x1000, None, None) == sb.STEM_ERR_UNSUPPORTED
     # an empty batch entry list is fine on the host and launches nothing
     empty = make_shape([0, 0])
     assert sb.stem_rows(empty) == (0, 0)
     assert L.stem_pool(empty.ref(), 0x1000, 0x1000, 0x1000, 1, 0x1000, 1 << 20, None) == sb.STEM_OK
-    assert L.stem_sparse_attn(empty.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 4, 0.1, 0x1000, None, None) == sb.STEM_OK
+    assert L.stem_sparse_attn(empty.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 4, 0, 0.1, 0x1000, None, None) == sb.STEM_OK
     with pytest.raises(sb.StemError):
         sb.stem_rows(make_shape([0, 640], d=64))
