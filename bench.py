@@ -28,8 +28,8 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
 # HBM-side bytes per sparse-attention launch on the 128K layer, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script (profiles/sparse_attn_kernel_llama8b_128k.md): FETCH_SIZE
-# 6.894e6 KiB x 2.0 (copy calibration) + WRITE_SIZE 1.049e6 KiB x 1.0.  Only valid for that workload.
-MEASURED_ATTN_TRAFFIC_BYTES = {"llama8b_128k": 15.2e9}
+# 5.715e6 KiB x 2.0 (copy calibration) + WRITE_SIZE 1.049e6 KiB x 1.0.  Only valid for that workload.
+MEASURED_ATTN_TRAFFIC_BYTES = {"llama8b_128k": 12.8e9}
 
 
 def median(xs):
