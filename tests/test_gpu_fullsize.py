@@ -108,3 +108,12 @@ def test_budget_sweep_64k_uniform_control():
 
 def test_packed_varlen_128k():
     full_size_case(wl.PACKED_128K, 16, heads=[2, 17, 28])
+
+
+def test_most_blocks_per_sequence_b64_ragged():
+    """STEM_MAX_BLOCKS key blocks in one sequence (B = 64, 262 127 tokens, partial last block): the
+    widest selection rows (64 keys per lane), the most score tiles, the longest causal ramp."""
+    w = wl.small("max_blocks_b64", seed=51, num_q_heads=2, num_kv_heads=1, seq_lens=(4096 * 64 - 17,),
+                 block_size=64, k_start=(40,), n_sink=2, n_local=2, outliers=(32,))
+    assert so.total_rows(w.cu_seqlens, w.block_size) == (4096, 4096)
+    full_size_case(w, 10, heads=[0, 1])

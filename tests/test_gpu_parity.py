@@ -33,6 +33,10 @@ SMALL = {
     # paper preset windows (4 initial + 4 local, minimum budget) on a short sequence
     "preset_b128": wl.small("preset_b128", seed=24, num_q_heads=4, num_kv_heads=1, seq_lens=(4096,),
                             block_size=128, k_start=(6.4,), n_sink=4, n_local=4, outliers=(3,), k_min=10),
+    # the largest batch: 64 sequences of 0..300 tokens (empty ones and single tokens included)
+    "batch64_b64": wl.small("batch64_b64", seed=26, num_q_heads=4, num_kv_heads=2,
+                            seq_lens=tuple([0, 1, 64, 65, 300, 2] + [(37 * x) % 301 for x in range(58)]),
+                            block_size=64, k_start=tuple([2] * 64), n_sink=1, n_local=1, outliers=tuple([1] * 64)),
     # no forced windows at all, uniform budget
     "noforce_b64": wl.small("noforce_b64", seed=25, num_q_heads=2, num_kv_heads=1, seq_lens=(2048, 1024),
                             block_size=64, k_start=(5, 3), n_sink=0, n_local=1, outliers=(2, 2), mu=1.0),
