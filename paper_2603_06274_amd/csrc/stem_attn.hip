@@ -120,18 +120,31 @@ __device__ __forceinline__ void sparse_attn_body(
     const int32_t* __restrict__ counts, const int32_t* __restrict__ indices,
     uint16_t* __restrict__ out, float* __restrict__ lse, const SeqTable& seq, int Hq, int R, int G,
     int T, int kmax, bool shared_lists, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh,
-    float scale, int items_per_xcd, unsigned char* __restrict__ k_lds, unsigned char* __restrict__ v_lds) {
+    float scale, int items_per_xcd, int xcds_per_kv_head, unsigned char* __restrict__ k_lds,
+    unsigned char* __restrict__ v_lds) {
     constexpr int KT = B / 32;                         // 32-key tiles per block
 
-    // ---- which (head, row): consecutive workgroup ids go to different XCDs, so give every XCD a
-    // contiguous range of the (kv head, row descending, head in group) order ----
+    // ---- which (head, row): consecutive workgroup ids go to different XCDs (each with its own
+    // L2), so an XCD should see few KV heads, and all XCDs equal work.  With xcds_per_kv_head = m > 0
+    // (Hkv divides 8) XCD x serves KV head x / m and every m-th row of it, rows descending (long
+    // rows first), the G heads of a group side by side; otherwise every XCD takes a contiguous
+    // range of the (KV head, row descending, head in group) order ----
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int64_t item = (int64_t)xcd * items_per_xcd + slot;
-    if (slot >= items_per_xcd || item >= (int64_t)Hq * R) return;
-    const int g = (int)(item / ((int64_t)R * G));
-    const int rem = (int)(item - (int64_t)g * R * G);
-    const int r = R - 1 - rem / G;
-    const int h = g * G + rem % G;
+    int g, r, h;
+    if (xcds_per_kv_head > 0) {
+        const int rank = (slot / G) * xcds_per_kv_head + xcd % xcds_per_kv_head;
+        if (slot >= items_per_xcd || rank >= R) return;
+        g = xcd / xcds_per_kv_head;
+        r = R - 1 - rank;
+        h = g * G + slot % G;
+    } else {
+        const int64_t item = (int64_t)xcd * items_per_xcd + slot;
+        if (slot >= items_per_xcd || item >= (int64_t)Hq * R) return;
+        g = (int)(item / ((int64_t)R * G));
+        const int rem = (int)(item - (int64_t)g * R * G);
+        r = R - 1 - rem / G;
+        h = g * G + rem % G;
+    }
 
     const int s = seq_of_row(seq, r);
     const int ic = r - seq.row_start[s];               // row inside the call's chunk of the sequence
@@ -153,13 +166,15 @@ __device__ __forceinline__ void sparse_attn_body(
     const uint16_t* k_head = k + (int64_t)g * kv_sh;
     const uint16_t* v_head = v + (int64_t)g * kv_sh;
 
-    // per-lane byte offsets of the block requests (see request_block)
+    // per-lane byte offsets of the block requests (BlockRequest): lane l of wave w fetches the
+    // 16-byte chunk that belongs at chunk l%16 of row 4w + l/16 of its slice, i.e. the swizzle is
+    // applied to the global column
     const int64_t row_bytes = kv_st * 2;
     const int lrow = w * 4 + (lane >> 4), pc = lane & 15;
     const uint32_t lane_row_off = (uint32_t)(lrow * row_bytes);
-    uint32_t k_off_even = lane_row_off + ((pc ^ (lrow & 15)) << 4);
-    uint32_t k_off_odd = (B == 128) ? k_off_even : lane_row_off + ((pc ^ ((lrow + 8) & 15)) << 4);
-    uint32_t v_off = lane_row_off + ((pc ^ ((lrow & 3) << 2)) << 4);
+    const uint32_t k_off_even = lane_row_off + ((pc ^ (lrow & 15)) << 4);
+    const uint32_t k_off_odd = (B == 128) ? k_off_even : lane_row_off + ((pc ^ ((lrow + 8) & 15)) << 4);
+    const uint32_t v_off = lane_row_off + ((pc ^ ((lrow & 3) << 2)) << 4);
     const auto k_rsrc = sequence_resource(k_head + (int64_t)seq_lo * kv_st, seq_hi - seq_lo, row_bytes);
     const auto v_rsrc = sequence_resource(v_head + (int64_t)seq_lo * kv_st, seq_hi - seq_lo, row_bytes);
     const uint32_t block_bytes = (uint32_t)(B * row_bytes);
@@ -455,11 +470,11 @@ __global__ __launch_bounds__(B * 2, 2) void sparse_attn_kernel(
     const int32_t* __restrict__ counts, const int32_t* __restrict__ indices,
     uint16_t* __restrict__ out, float* __restrict__ lse, SeqTable seq, int Hq, int R, int G, int T,
     int kmax, bool shared_lists, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh, float scale,
-    int items_per_xcd) {
+    int items_per_xcd, int xcds_per_kv_head) {
     __shared__ __attribute__((aligned(1024))) unsigned char k_lds[B * kRowBytes];
     __shared__ __attribute__((aligned(1024))) unsigned char v_lds[B * kRowBytes];
     sparse_attn_body<B>(q, k, v, counts, indices, out, lse, seq, Hq, R, G, T, kmax, shared_lists, q_st, q_sh,
-                        kv_st, kv_sh, scale, items_per_xcd, k_lds, v_lds);
+                        kv_st, kv_sh, scale, items_per_xcd, xcds_per_kv_head, k_lds, v_lds);
 }
 
 int launch_sparse_attn(const Problem& p, const void* q, const void* k, const void* v,
@@ -473,7 +488,10 @@ int launch_sparse_attn(const Problem& p, const void* q, const void* k, const voi
         if (rows > 0 && (rows - 1) * p.kv_st * 2 + kHeadDim * 2 > 0x7fffffffll) return STEM_ERR_UNSUPPORTED;
     }
     const int64_t items = (int64_t)p.Hq * p.R;
-    const int64_t per_xcd = (items + 7) / 8;
+    const int xcds_per_kv_head = (p.Hkv <= 8 && 8 % p.Hkv == 0) ? 8 / p.Hkv : 0;
+    const int64_t per_xcd = xcds_per_kv_head > 0
+                                ? (int64_t)((p.R + xcds_per_kv_head - 1) / xcds_per_kv_head) * p.G
+                                : (items + 7) / 8;
     if (per_xcd * 8 > 0x7fffffff) return STEM_ERR_UNSUPPORTED;
     dim3 grid((unsigned)(per_xcd * 8));
     const uint16_t* qq = static_cast<const uint16_t*>(q);
@@ -483,11 +501,11 @@ int launch_sparse_attn(const Problem& p, const void* q, const void* k, const voi
     if (p.B == 128)
         hipLaunchKernelGGL(sparse_attn_kernel<128>, grid, dim3(256), 0, stream, qq, kk, vv, counts,
                            indices, oo, lse, p.seq, p.Hq, p.R, p.G, p.T, kmax, lists_per_kv_head, p.q_st, p.q_sh,
-                           p.kv_st, p.kv_sh, softmax_scale, (int)per_xcd);
+                           p.kv_st, p.kv_sh, softmax_scale, (int)per_xcd, xcds_per_kv_head);
     else
         hipLaunchKernelGGL(sparse_attn_kernel<64>, grid, dim3(128), 0, stream, qq, kk, vv, counts,
                            indices, oo, lse, p.seq, p.Hq, p.R, p.G, p.T, kmax, lists_per_kv_head, p.q_st, p.q_sh,
-                           p.kv_st, p.kv_sh, softmax_scale, (int)per_xcd);
+                           p.kv_st, p.kv_sh, softmax_scale, (int)per_xcd, xcds_per_kv_head);
     return check_launch();
 }
 

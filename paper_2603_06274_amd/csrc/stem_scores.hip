@@ -157,19 +157,23 @@ __global__ __launch_bounds__(256) void group_scores_kernel(const float* __restri
                                                            float* __restrict__ group_scores,
                                                            int64_t per_head, int G, int take_mean,
                                                            int64_t total) {
-    const int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;   // per_head % 4 == 0 or scalar tail
+    const int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;   // per_head % 4 == 0
     if (idx >= total) return;
     const int64_t g = idx / per_head, off = idx - g * per_head;
     const float* src = scores + g * G * per_head + off;
-    const int n = (int)min((int64_t)4, per_head - off);
-    float acc[4];
-    for (int e = 0; e < n; ++e) acc[e] = src[e];
-    for (int x = 1; x < G; ++x)
-        for (int e = 0; e < n; ++e) {
-            const float y = src[(int64_t)x * per_head + e];
-            acc[e] = take_mean ? acc[e] + y : fmaxf(acc[e], y);
-        }
-    for (int e = 0; e < n; ++e) group_scores[idx + e] = take_mean ? acc[e] / (float)G : acc[e];
+    float4 acc = *reinterpret_cast<const float4*>(src);
+    for (int x = 1; x < G; ++x) {
+        const float4 y = *reinterpret_cast<const float4*>(src + (int64_t)x * per_head);
+        acc.x = take_mean ? acc.x + y.x : fmaxf(acc.x, y.x);
+        acc.y = take_mean ? acc.y + y.y : fmaxf(acc.y, y.y);
+        acc.z = take_mean ? acc.z + y.z : fmaxf(acc.z, y.z);
+        acc.w = take_mean ? acc.w + y.w : fmaxf(acc.w, y.w);
+    }
+    if (take_mean) {
+        const float inv = (float)G;
+        acc.x /= inv; acc.y /= inv; acc.z /= inv; acc.w /= inv;
+    }
+    *reinterpret_cast<float4*>(group_scores + idx) = acc;
 }
 
 int launch_group_scores(const Problem& p, const float* scores, int reduce, float* group_scores,
@@ -177,11 +181,10 @@ int launch_group_scores(const Problem& p, const float* scores, int reduce, float
     const int64_t per_head = (int64_t)p.R * p.NBmax;
     const int64_t total = per_head * p.Hkv;
     if (total == 0) return STEM_OK;
-    // a thread's four elements must not straddle two heads
-    if (per_head % 4) {
-        // rare shapes: fall back to one element per thread by widening the index space
-        const int64_t threads = total;
-        const int64_t blocks = (threads + 255) / 256;
+    // four elements per thread when they cannot straddle two heads and the rows are 16-byte
+    // aligned, else one
+    if (per_head % 4 || (reinterpret_cast<uintptr_t>(scores) | reinterpret_cast<uintptr_t>(group_scores)) & 15) {
+        const int64_t blocks = (total + 255) / 256;
         if (blocks > 0x7fffffff) return STEM_ERR_UNSUPPORTED;
         hipLaunchKernelGGL(group_scores_scalar_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, scores,
                            group_scores, per_head, p.G, reduce == STEM_GROUP_MEAN, total);
