@@ -181,6 +181,20 @@ int stem_select(const stem_shape* shape, const float* scores, const int32_t* bud
                 int32_t* indices, int32_t kmax, void* hip_stream);
 
 /*
+ * Stages 1 and 2 in one call that never writes the score tensor: stem_pool, then one kernel that
+ * computes the metric of a band of rows into on-chip memory and selects from there.  Same results
+ * as stem_estimate followed by stem_select with lists_per_kv_head = 0, up to the rounding order of
+ * the fp32 score sums (near-ties may resolve differently).  debug_scores, if not NULL, is a device
+ * fp32 [Hq, R, NBmax] buffer that receives the scores the selection saw (for checking; it defeats
+ * the purpose otherwise).  Arguments as for the two calls it replaces.
+ */
+int stem_estimate_select(const stem_shape* shape, const void* q, const void* k, const void* v,
+                         float beta, float route_scale, int32_t ad_stride, const int32_t* budget,
+                         int32_t n_sink, int32_t n_local, int32_t* counts, int32_t* indices,
+                         int32_t kmax, float* debug_scores, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
+
+/*
  * Stage 3, Algorithm 1 step 3d: for every head h, row r and valid query token t of the row's block
  *   out[t, h, :] = sum_u softmax_u( softmax_scale * <Q[t,h], K[u,g]> ) V[u,g]
  * over the tokens u <= t of the key blocks indices[h, r, 0 .. counts[h,r]) (of indices[h / G, r, ..]

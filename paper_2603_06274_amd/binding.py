@@ -69,6 +69,7 @@ def lib() -> ctypes.CDLL:
             "stem_block_scores": [shp, vp, sz, i32, f32, f32, vp, vp],
             "stem_estimate": [shp, vp, vp, vp, f32, f32, i32, vp, vp, sz, vp],
             "stem_group_scores": [shp, vp, i32, vp, vp],
+            "stem_estimate_select": [shp, vp, vp, vp, f32, f32, i32, vp, i32, i32, vp, vp, i32, vp, vp, sz, vp],
             "stem_select": [shp, vp, vp, i32, i32, i32, vp, vp, i32, vp],
             "stem_sparse_attn": [shp, vp, vp, vp, vp, vp, i32, i32, f32, vp, vp, vp],
         }
@@ -82,7 +83,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTED = ["stem_version", "stem_strerror", "stem_rows", "stem_workspace_bytes",
             "stem_workspace_layout", "stem_budget_schedule", "stem_pool", "stem_block_scores",
-            "stem_group_scores",
+            "stem_group_scores", "stem_estimate_select",
             "stem_estimate", "stem_select", "stem_sparse_attn"]
 
 
@@ -195,6 +196,17 @@ def stem_estimate(shape: Shape, q, k, v, beta: float, route_scale: float, ad_str
 
 
 STEM_GROUP_MAX, STEM_GROUP_MEAN = 0, 1
+
+
+def stem_estimate_select(shape: Shape, q, k, v, beta: float, route_scale: float, ad_stride: int,
+                         budget: torch.Tensor, n_sink: int, n_local: int, counts: torch.Tensor,
+                         indices: torch.Tensor, kmax: int, debug_scores: Optional[torch.Tensor],
+                         workspace: torch.Tensor) -> None:
+    _check(lib().stem_estimate_select(shape.ref(), _ptr(q), _ptr(k), _ptr(v), float(beta), float(route_scale),
+                                      int(ad_stride), _ptr(budget), int(n_sink), int(n_local), _ptr(counts),
+                                      _ptr(indices), int(kmax), _ptr(debug_scores), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream()),
+           "stem_estimate_select")
 
 
 def stem_group_scores(shape: Shape, scores: torch.Tensor, reduce: int, group_scores: torch.Tensor) -> None:

@@ -246,6 +246,31 @@ int stem_estimate(const stem_shape* shape, const void* q, const void* k, const v
                              hip_stream);
 }
 
+int stem_estimate_select(const stem_shape* shape, const void* q, const void* k, const void* v,
+                         float beta, float route_scale, int32_t ad_stride, const int32_t* budget,
+                         int32_t n_sink, int32_t n_local, int32_t* counts, int32_t* indices,
+                         int32_t kmax, float* debug_scores, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+    if (!std::isfinite(beta) || !std::isfinite(route_scale)) return STEM_ERR_INVALID_ARG;
+    Problem p;
+    int st = make_problem(shape, &p);
+    if (st != STEM_OK) return st;
+    if ((st = check_ad_stride(p, ad_stride)) != STEM_OK) return st;
+    if (!budget || !counts || !indices) return STEM_ERR_INVALID_ARG;
+    if (debug_scores && !aligned16(debug_scores)) return STEM_ERR_INVALID_ARG;
+    if (n_sink < 0 || n_local < 0 || kmax < 1) return STEM_ERR_INVALID_ARG;
+    if ((int64_t)kmax < (int64_t)n_sink + n_local && kmax < p.NBmax) return STEM_ERR_INVALID_ARG;
+    st = stem_pool(shape, q, k, v, ad_stride, workspace, workspace_bytes, hip_stream);
+    if (st != STEM_OK || p.R == 0) return st;
+    WorkspaceLayout w = workspace_layout(p, ad_stride);
+    const char* ws = static_cast<const char*>(workspace);
+    return launch_score_select(p, ad_stride, reinterpret_cast<const float*>(ws + w.q_bar),
+                               reinterpret_cast<const float*>(ws + w.k_bar),
+                               reinterpret_cast<const float*>(ws + w.m_v), beta, route_scale, budget, n_sink,
+                               n_local, counts, indices, kmax, debug_scores,
+                               static_cast<hipStream_t>(hip_stream));
+}
+
 int stem_group_scores(const stem_shape* shape, const float* scores, int32_t reduce,
                       float* group_scores, void* hip_stream) {
     Problem p;

@@ -55,6 +55,10 @@ int launch_group_scores(const Problem& p, const float* scores, int reduce, float
 int launch_select(const Problem& p, int heads, const float* scores, const int32_t* budget,
                   int32_t n_sink, int32_t n_local, int32_t* counts, int32_t* indices, int32_t kmax,
                   hipStream_t stream);
+int launch_score_select(const Problem& p, int ad_stride, const float* q_bar, const float* k_bar,
+                        const float* m_v, float beta, float route_scale, const int32_t* budget,
+                        int32_t n_sink, int32_t n_local, int32_t* counts, int32_t* indices,
+                        int32_t kmax, float* debug_scores, hipStream_t stream);
 int launch_sparse_attn(const Problem& p, const void* q, const void* k, const void* v,
                        const int32_t* counts, const int32_t* indices, int32_t kmax,
                        bool lists_per_kv_head, float softmax_scale, void* out, float* lse,

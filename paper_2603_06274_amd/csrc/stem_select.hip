@@ -22,35 +22,25 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
     return __popcll(mask & ((1ull << lane) - 1ull));
 }
 
-template <int ITEMS>
-__global__ __launch_bounds__(kSelectThreads) void select_kernel(
-    const float* __restrict__ scores, const int32_t* __restrict__ budget,
-    int32_t* __restrict__ counts, int32_t* __restrict__ indices, SeqTable seq, int Hq, int R,
-    int NBmax, int n_sink, int n_local, int kmax) {
-    const int lane = threadIdx.x & 63;
-    const int64_t item = (int64_t)blockIdx.x * (kSelectThreads / 64) + (threadIdx.x >> 6);
-    if (item >= (int64_t)Hq * R) return;               // wave-uniform; the kernel has no barriers
-    const int h = (int)(item / R);
-    const int r = (int)(item - (int64_t)h * R);
-    const int s = seq_of_row(seq, r);
-    const int i = seq.first_block[s] + (r - seq.row_start[s]);   // block index in the sequence
-
+// The selection of one row by one wavefront.  load(j) returns the score of key block j of the row
+// (any memory); i is the row's block index in its sequence.
+template <int ITEMS, typename Load>
+__device__ __forceinline__ void select_row(Load load, int i, int row_budget, int n_sink, int n_local,
+                                           int kmax, int lane, int32_t* __restrict__ out,
+                                           int32_t* __restrict__ count_out) {
     const int fs = min(n_sink, i + 1);                 // forced head: blocks [0, fs)
     const int fe = max(fs, i - n_local + 1);           // forced tail: blocks [fe, i]
     const int nfree = fe - fs;
     const int forced = i + 1 - nfree;
-    int k = max(budget[r], forced);
+    int k = max(row_budget, forced);
     k = min(k, min(i + 1, kmax));
     const int need = max(0, k - forced);               // free blocks to pick, <= nfree
-
-    const float* row = scores + ((int64_t)h * R + r) * NBmax;
-    int32_t* out = indices + ((int64_t)h * R + r) * kmax;
 
     uint32_t key[ITEMS];
 #pragma unroll
     for (int e = 0; e < ITEMS; ++e) {
         const int j = fs + e * 64 + lane;
-        key[e] = (j < fe) ? ordered_key(row[j]) : 0u;  // 0 sorts below every real key
+        key[e] = (j < fe) ? ordered_key(load(j)) : 0u; // 0 sorts below every real key
     }
 
     uint32_t tau = 0;
@@ -92,7 +82,24 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(
     const int tail = min(i + 1 - fe, k - base);        // forced tail always fits: k >= forced
     for (int x = lane; x < tail; x += 64) out[base + x] = fe + x;
     for (int x = k + lane; x < kmax; x += 64) out[x] = -1;
-    if (lane == 0) counts[(int64_t)h * R + r] = k;
+    if (lane == 0) *count_out = k;
+}
+
+template <int ITEMS>
+__global__ __launch_bounds__(kSelectThreads) void select_kernel(
+    const float* __restrict__ scores, const int32_t* __restrict__ budget,
+    int32_t* __restrict__ counts, int32_t* __restrict__ indices, SeqTable seq, int Hq, int R,
+    int NBmax, int n_sink, int n_local, int kmax) {
+    const int lane = threadIdx.x & 63;
+    const int64_t item = (int64_t)blockIdx.x * (kSelectThreads / 64) + (threadIdx.x >> 6);
+    if (item >= (int64_t)Hq * R) return;               // wave-uniform; the kernel has no barriers
+    const int h = (int)(item / R);
+    const int r = (int)(item - (int64_t)h * R);
+    const int s = seq_of_row(seq, r);
+    const int i = seq.first_block[s] + (r - seq.row_start[s]);   // block index in the sequence
+    const float* row = scores + ((int64_t)h * R + r) * NBmax;
+    select_row<ITEMS>([&](int j) { return row[j]; }, i, budget[r], n_sink, n_local, kmax, lane,
+                      indices + ((int64_t)h * R + r) * kmax, counts + (int64_t)h * R + r);
 }
 
 int launch_select(const Problem& p, int heads, const float* scores, const int32_t* budget,
@@ -110,6 +117,174 @@ int launch_select(const Problem& p, int heads, const float* scores, const int32_
     else if (p.NBmax <= 64 * 64) STEM_SELECT_LAUNCH(64);
     else return STEM_ERR_UNSUPPORTED;
 #undef STEM_SELECT_LAUNCH
+    return check_launch();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Fused metric + selection: the scores of a band of query-block rows are computed into LDS and
+// selected from there, so the [Hq, R, NBmax] score tensor never exists in HBM.
+//
+// One workgroup owns (head h, band of ROWS consecutive rows of one sequence).  Phase 1 walks the
+// key blocks the band can see in chunks of 128: the chunk's pooled keys and the band's pooled
+// queries are staged through LDS 16 floats of the contraction at a time; wave w accumulates rows
+// 4w .. 4w+3 (ROWS = 16) or row w (ROWS = 4) of the band against the 128 keys, two adjacent keys
+// per lane, in fp32 FMAs (one 8-byte read of key values and one wave-wide broadcast of query
+// values per step).  Phase 2: every wave runs select_row on its rows with the scores read from LDS.
+// ROWS = 16 serves up to 1024 key blocks per row (16 x 1024 fp32 = 64 KiB of LDS), ROWS = 4 up to 4096.
+// ------------------------------------------------------------------------------------------------
+struct BandTable {
+    int32_t band_start[STEM_MAX_BATCH + 1];            // prefix sums of ceil(rows of the call / ROWS)
+};
+
+constexpr int kBandChunk = 16;                         // floats of the contraction staged per step
+constexpr int kBandKeys = 128;                         // key blocks per step
+
+template <int ROWS>
+__global__ __launch_bounds__(256) void score_select_kernel(
+    const float* __restrict__ q_bar, const float* __restrict__ k_bar, const float* __restrict__ m_v,
+    const int32_t* __restrict__ budget, int32_t* __restrict__ counts, int32_t* __restrict__ indices,
+    float* __restrict__ debug_scores, SeqTable seq, BandTable bands, int R, int Rk, int NBmax, int G,
+    int S, float beta, float route_scale, int n_sink, int n_local, int kmax) {
+    constexpr int NBcap = ROWS == 16 ? 1024 : 4096;    // key blocks per row held in LDS
+    constexpr int RPW = ROWS / 4;                      // rows per wave
+    constexpr int ITEMS = NBcap / 64;
+    __shared__ float sc[ROWS][NBcap];                  // 64 KiB
+    __shared__ __attribute__((aligned(16))) float ks[kBandChunk][kBandKeys + 2];   // [contraction][key]
+    __shared__ __attribute__((aligned(16))) float qs[kBandChunk][ROWS];            // [contraction][row]
+
+    // bands are handed out last first: within a sequence the later bands see more keys and take longer
+    const int band = bands.band_start[seq.batch] - 1 - (int)blockIdx.x;
+    int s = 0;
+    for (int x = 1; x < seq.batch; ++x) s = (band >= bands.band_start[x]) ? x : s;
+    const int row0 = seq.row_start[s];
+    const int n_rows = seq.row_start[s + 1] - row0;    // rows of this sequence in the call
+    const int first = seq.first_block[s];
+    const int krow0 = seq.key_row_start[s];
+    const int ic0 = (band - bands.band_start[s]) * ROWS;   // first row of the band, call-local
+    const int band_rows = min(ROWS, n_rows - ic0);
+    const int n_keys = first + ic0 + band_rows;        // key blocks the band's last row can see
+    const int h = blockIdx.y, g = h / G;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int depth = S * kHeadDim;
+    const float neg_inf = -__builtin_huge_valf();
+
+    const float* a_src = q_bar + ((int64_t)h * R + row0 + ic0) * depth;
+    const float* b_src = k_bar + ((int64_t)g * Rk + krow0) * depth;
+
+    // ---- phase 1: scores of the band into LDS.  The (key chunk, contraction slice) steps run as one
+    // sequence with the next step's global loads in flight while the current one is computed ----
+    const int slices = depth / kBandChunk;             // per key chunk
+    const int steps = (n_keys + kBandKeys - 1) / kBandKeys * slices;
+    float4 bv[2], av;
+    auto fetch = [&](int step) {
+        const int j0 = (step / slices) * kBandKeys, kc = (step % slices) * kBandChunk;
+        // a slice lies inside one residue class a of the query block; its partner is class S-1-a
+        const int kb = (S - 1 - (kc >> 7)) * kHeadDim + (kc & (kHeadDim - 1));
+        // keys: 128 rows x 16 floats = 512 float4, two per thread; queries: ROWS x 16 floats
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = tid + 256 * u;
+            const int row = idx >> 2, c4 = (idx & 3) * 4;
+            bv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (j0 + row < n_keys) bv[u] = *reinterpret_cast<const float4*>(b_src + (int64_t)(j0 + row) * depth + kb + c4);
+        }
+        av = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (tid < ROWS * 4 && (tid >> 2) < band_rows)
+            av = *reinterpret_cast<const float4*>(a_src + (int64_t)(tid >> 2) * depth + kc + (tid & 3) * 4);
+    };
+    float acc[RPW][2];
+#pragma unroll
+    for (int x = 0; x < RPW; ++x) acc[x][0] = acc[x][1] = 0.f;
+    if (steps > 0) fetch(0);
+    for (int step = 0; step < steps; ++step) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int idx = tid + 256 * u;
+            const int row = idx >> 2, c4 = (idx & 3) * 4;
+            ks[c4 + 0][row] = bv[u].x; ks[c4 + 1][row] = bv[u].y; ks[c4 + 2][row] = bv[u].z; ks[c4 + 3][row] = bv[u].w;
+        }
+        if (tid < ROWS * 4) {
+            const int row = tid >> 2, c4 = (tid & 3) * 4;
+            qs[c4 + 0][row] = av.x; qs[c4 + 1][row] = av.y; qs[c4 + 2][row] = av.z; qs[c4 + 3][row] = av.w;
+        }
+        __syncthreads();
+        if (step + 1 < steps) fetch(step + 1);
+#pragma unroll
+        for (int kk = 0; kk < kBandChunk; ++kk) {
+            const float2 kv = *reinterpret_cast<const float2*>(&ks[kk][2 * lane]);
+#pragma unroll
+            for (int x = 0; x < RPW; ++x) {
+                const float qv = qs[kk][w * RPW + x];
+                acc[x][0] = fmaf(qv, kv.x, acc[x][0]);
+                acc[x][1] = fmaf(qv, kv.y, acc[x][1]);
+            }
+        }
+        __syncthreads();
+        if (step % slices == slices - 1) {             // the chunk's contraction is complete
+            const int j0 = (step / slices) * kBandKeys;
+#pragma unroll
+            for (int y = 0; y < 2; ++y) {
+                const int j = j0 + 2 * lane + y;
+                const float mag = (j < n_keys) ? beta * fmaxf(0.f, m_v[(int64_t)g * Rk + krow0 + j]) : 0.f;
+#pragma unroll
+                for (int x = 0; x < RPW; ++x) {
+                    const int row = w * RPW + x;
+                    const float val = (j <= first + ic0 + row) ? fmaf(route_scale / (float)S, acc[x][y], mag) : neg_inf;
+                    acc[x][y] = 0.f;
+                    if (row >= band_rows || j >= NBcap) continue;
+                    sc[row][j] = val;
+                    if (debug_scores != nullptr && j < NBmax)
+                        debug_scores[((int64_t)h * R + row0 + ic0 + row) * NBmax + j] = val;
+                }
+            }
+        }
+    }
+    // the rest of a debug row is -inf, as in the unfused score tensor
+    if (debug_scores != nullptr) {
+        const int done = (n_keys + kBandKeys - 1) / kBandKeys * kBandKeys;
+        for (int x = 0; x < RPW; ++x) {
+            const int row = w * RPW + x;
+            if (row >= band_rows) continue;
+            for (int j = done + lane; j < NBmax; j += 64)
+                debug_scores[((int64_t)h * R + row0 + ic0 + row) * NBmax + j] = neg_inf;
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 2: selection from LDS, one row at a time per wave ----
+    for (int x = 0; x < RPW; ++x) {
+        const int row = w * RPW + x;
+        if (row >= band_rows) break;                   // wave-uniform
+        const int r = row0 + ic0 + row;
+        const float* scr = sc[row];
+        select_row<ITEMS>([&](int j) { return scr[j]; }, first + ic0 + row, budget[r], n_sink, n_local, kmax,
+                          lane, indices + ((int64_t)h * R + r) * kmax, counts + (int64_t)h * R + r);
+    }
+}
+
+int launch_score_select(const Problem& p, int ad_stride, const float* q_bar, const float* k_bar,
+                        const float* m_v, float beta, float route_scale, const int32_t* budget,
+                        int32_t n_sink, int32_t n_local, int32_t* counts, int32_t* indices,
+                        int32_t kmax, float* debug_scores, hipStream_t stream) {
+    if (p.NBmax > 4096) return STEM_ERR_UNSUPPORTED;
+    const int rows_per_band = p.NBmax <= 1024 ? 16 : 4;
+    BandTable bands;
+    int total = 0;
+    for (int s = 0; s <= STEM_MAX_BATCH; ++s) {
+        bands.band_start[s] = total;
+        if (s < p.batch) total += (p.seq.row_start[s + 1] - p.seq.row_start[s] + rows_per_band - 1) / rows_per_band;
+    }
+    if (total == 0) return STEM_OK;
+    if (p.Hq > 65535) return STEM_ERR_UNSUPPORTED;
+    dim3 grid(total, p.Hq), block(256);
+    if (rows_per_band == 16)
+        hipLaunchKernelGGL(score_select_kernel<16>, grid, block, 0, stream, q_bar, k_bar, m_v, budget, counts,
+                           indices, debug_scores, p.seq, bands, p.R, p.Rk, p.NBmax, p.G, ad_stride, beta,
+                           route_scale, n_sink, n_local, kmax);
+    else
+        hipLaunchKernelGGL(score_select_kernel<4>, grid, block, 0, stream, q_bar, k_bar, m_v, budget, counts,
+                           indices, debug_scores, p.seq, bands, p.R, p.Rk, p.NBmax, p.G, ad_stride, beta,
+                           route_scale, n_sink, n_local, kmax);
     return check_launch();
 }
 

@@ -80,9 +80,19 @@ class StemPrefill:
         sb.stem_sparse_attn(self.shape, self.q, self.k, self.v, self.counts, self.indices, self.kmax,
                             self.softmax_scale, self.out, self.lse, lists_per_kv_head=bool(self.group_share))
 
-    def run(self) -> torch.Tensor:
-        self.estimate()
-        self.select()
+    def estimate_select(self, debug_scores: Optional[torch.Tensor] = None) -> None:
+        """Stages 1-2 without the score tensor (per-head lists only)."""
+        assert not self.group_share
+        sb.stem_estimate_select(self.shape, self.q, self.k, self.v, self.beta, self.route_scale,
+                                self.ad_stride, self.budget, self.n_sink, self.n_local, self.counts,
+                                self.indices, self.kmax, debug_scores, self.workspace)
+
+    def run(self, fused: bool = False) -> torch.Tensor:
+        if fused:
+            self.estimate_select()
+        else:
+            self.estimate()
+            self.select()
         self.attend()
         return self.out
 

@@ -110,6 +110,36 @@ def test_packed_varlen_128k():
     full_size_case(wl.PACKED_128K, 16, heads=[2, 17, 28])
 
 
+def test_fused_estimate_select_128k_and_most_blocks():
+    """The fused stage 1-2 at the headline size (16-row bands) and at 4096 key blocks (4-row bands):
+    lists against the oracle, and the whole chained output against the unfused path's."""
+    big = wl.small("max_blocks_b64", seed=51, num_q_heads=2, num_kv_heads=1, seq_lens=(4096 * 64 - 17,),
+                   block_size=64, k_start=(40,), n_sink=2, n_local=2, outliers=(32,))
+    for w in (wl.LLAMA_128K, big):
+        say("case", w.name, "fused")
+        data, qkv = tensors_for(w)
+        pf = pu.device_prefill(w, data)
+        pf.run(fused=True)
+        torch.cuda.synchronize()
+        scores = pu.oracle_estimate(w, qkv)[3]
+        _, counts, indices = pu.oracle_select(w, scores)
+        same = pu.check_lists(w, pf.counts.cpu().numpy(), pf.indices.cpu().numpy(), counts, indices, scores, say)
+        assert same.mean() > 0.99
+        fused_out, fused_counts, fused_idx = pf.out.clone(), pf.counts.clone(), pf.indices.clone()
+        pf.run(fused=False)
+        torch.cuda.synchronize()
+        agree = (fused_idx == pf.indices).all(dim=2) & (fused_counts == pf.counts)      # [Hq, R]
+        assert agree.float().mean().item() > 0.99
+        B = w.block_size
+        for (lo, hi, nb, row0) in so.sequence_table(w.cu_seqlens, B):
+            rows_ok = agree[:, row0:row0 + nb].all(dim=0).cpu().numpy()
+            for i in np.nonzero(rows_ok)[0]:
+                t0, t1 = lo + i * B, min(lo + (i + 1) * B, hi)
+                assert torch.equal(fused_out[t0:t1], pf.out[t0:t1])
+        del pf
+        torch.cuda.empty_cache()
+
+
 def test_most_blocks_per_sequence_b64_ragged():
     """STEM_MAX_BLOCKS key blocks in one sequence (B = 64, 262 127 tokens, partial last block): the
     widest selection rows (64 keys per lane), the most score tiles, the longest causal ramp."""

@@ -177,6 +177,32 @@ def test_chunked_prefill_gives_the_rows_of_the_one_piece_call():
     pu.check_output(out, o_out, w.name)
 
 
+@pytest.mark.parametrize("ad_stride", [1, 4])
+@pytest.mark.parametrize("name", ["ragged_b64", "packed_b128", "long_b128", "batch64_b64", "noforce_b64"])
+def test_fused_estimate_select(name, ad_stride):
+    """Stages 1-2 without the score tensor: the scores the fused kernel saw (debug dump) and its
+    lists against the oracle; the same lists with and without the dump."""
+    w = SMALL[name]
+    say("case", w.name, "seed", w.seed, "fused, ad_stride", ad_stride)
+    data = wl.generate(w)
+    qkv = pu.host_arrays(data)
+    pf = pu.device_prefill(w, data, ad_stride=ad_stride)
+    dump = torch.full_like(pf.scores, float("nan"))
+    pf.estimate_select(dump)
+    torch.cuda.synchronize()
+    counts_dbg, idx_dbg = pf.counts.clone(), pf.indices.clone()
+    q_bar, k_bar, m_v, scores = pu.oracle_estimate(w, qkv, ad_stride)
+    pu.check_pooled(pf, q_bar, k_bar, m_v)
+    pu.check_scores(dump.cpu().numpy(), scores)
+    _, counts, indices = pu.oracle_select(w, scores)
+    pu.check_lists(w, counts_dbg.cpu().numpy(), idx_dbg.cpu().numpy(), counts, indices, scores, say)
+    pf.counts.fill_(-7)
+    pf.indices.fill_(-7)
+    pf.estimate_select(None)
+    torch.cuda.synchronize()
+    assert torch.equal(pf.counts, counts_dbg) and torch.equal(pf.indices, idx_dbg)
+
+
 @pytest.mark.parametrize("how", ["max", "mean"])
 @pytest.mark.parametrize("name", ["packed_b128", "ragged_b64"])
 def test_group_shared_selection(name, how):
