@@ -111,6 +111,49 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t sequence_resource(const uint16
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(first_row), 0, (int)bytes, 0x00020000);
 }
 
+// When the softmax pairs of a block are issued and where its reference may be checked, for KT
+// 32-key tiles per block.  Slot s = 0 .. 2*NS-1 counts the wave's matrix instructions of one block
+// (S^T first, then O^T).  Pair q = 8*t + x/2 may be issued once tile t of S^T is complete (slot
+// 8t+7) and must be done before O^T reaches its 16 keys (slot NS + 8t + 4*((q%8)/4)).  At a check
+// slot every pair issued so far must be either consumed by O^T already or part of the window being
+// checked (the pairs issued since the previous check), so that moving the reference there leaves
+// no stale probability behind.  valid() states exactly that and is asserted at compile time.
+template <int KT>
+struct SoftmaxSchedule {
+    static constexpr int NS = KT * 8;                  // matrix instructions per product and block
+    static constexpr int NP = KT * 8;                  // accumulator pairs per block and lane
+    static constexpr int kChecks = KT == 4 ? 3 : 2;
+    static constexpr int check_slot(int c) { return c == 0 ? NS : c == 1 ? (KT == 4 ? 48 : 24) : 56; }
+    // pairs issued once slot `slot` is issued: four tiles - tiles 0..2 at two pairs per three slots
+    // from slot 8 on, tile 3 one per slot from slot 48 on; two tiles - one per slot from slot 8 on
+    static constexpr int pairs_by(int slot) {
+        if (slot < 8) return 0;
+        if (KT != 4) return slot - 7 > NP ? NP : slot - 7;
+        if (slot < 48) return ((slot - 7) * 2) / 3 > 24 ? 24 : ((slot - 7) * 2) / 3;
+        return 24 + (slot - 47) > NP ? NP : 24 + (slot - 47);
+    }
+    static constexpr bool valid() {
+        for (int s = 0; s < 2 * NS; ++s) {
+            const int before = s == 0 ? 0 : pairs_by(s - 1), now = pairs_by(s);
+            if (now < before || now > before + 1) return false;            // at most one pair per slot
+            if (now > before) {
+                const int q = before, t = q / 8;
+                if (s <= 8 * t + 7) return false;                            // its S^T tile is complete
+                if (s >= NS + 8 * t + 4 * ((q % 8) / 4)) return false;       // O^T has not reached it
+            }
+        }
+        int lo = 0;
+        for (int c = 0; c < kChecks; ++c) {
+            const int slot = check_slot(c);
+            if (slot < NS || slot % 4) return false;
+            if (lo > slot - NS) return false;          // pairs below the window are consumed (4 per 4 slots)
+            lo = pairs_by(slot - 1);
+        }
+        return lo == NP && pairs_by(2 * NS - 1) == NP;
+    }
+};
+static_assert(SoftmaxSchedule<4>::valid() && SoftmaxSchedule<2>::valid(), "softmax schedule");
+
 // The body takes the two LDS buffers as __restrict__ parameters: once inlined, every access carries
 // alias-scope information, which lets the compiler's wait-count insertion tell a read of one buffer
 // from an in-flight global->LDS load into the other (otherwise it waits for all of them).
@@ -263,20 +306,11 @@ __device__ __forceinline__ void sparse_attn_body(
 
     // The softmax of a block is 8*KT accumulator pairs per lane.  Vector and matrix instructions
     // of the SAME wave overlap well, those of two waves sharing a SIMD do not, so the pairs are
-    // spread over the wave's own matrix instructions: slot s = 0 .. 2*NS-1 counts them (S^T first,
-    // then O^T), pair q = 8*t + x/2 may be issued once tile t of S^T is complete (slot 8t+7) and
-    // must be done before O^T reaches its 16 keys (slot NS + 8t + 4*((q%8)/4)).  For four tiles the
-    // pairs go out at two per three slots from slot 8 on, for two tiles at one per slot.
-    constexpr int NS = KT * 8;                         // matrix instructions per product and block
-    constexpr int NP = KT * 8;                         // accumulator pairs per block and lane
-    auto pairs_by = [](int slot) {                     // pairs issued once slot `slot` is issued
-        const int c = slot < 8 ? 0 : (KT == 4 ? ((slot - 7) * 2) / 3 : slot - 7);
-        return c > NP ? NP : c;
-    };
-    // The reference of the softmax can only be checked where a run of pairs is complete and not
-    // yet consumed: at these slot boundaries ("windows" of pairs between them).
-    constexpr int kChecks = KT == 4 ? 3 : 2;
-    constexpr int kCheckSlot[3] = {NS, KT == 4 ? 48 : 24, 56};
+    // spread over the wave's own matrix instructions (SoftmaxSchedule).
+    using Sched = SoftmaxSchedule<KT>;
+    constexpr int NS = Sched::NS, kChecks = Sched::kChecks;
+    auto pairs_by = [](int slot) { return Sched::pairs_by(slot); };
+    constexpr int kCheckSlot[3] = {Sched::check_slot(0), Sched::check_slot(1), Sched::check_slot(2)};
 
     f32x16_t s_acc[KT];
     uint32_t p_pk[KT][8];                              // bf16 pairs: [tile][16-key step * 4 + pair]

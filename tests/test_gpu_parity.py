@@ -307,6 +307,56 @@ def test_attention_on_given_lists_full_budget_and_random():
         assert np.abs(lse.cpu().numpy() - o_lse).max() <= 5e-3
 
 
+def test_attention_reference_moves_and_unusable_entries():
+    """Two things ordinary data does not reach.  (1) Logits far outside the exponent range of a
+    fixed reference, growing along the keys and jumping inside blocks, so that the softmax reference
+    has to move at every check point of a block (and O is rescaled) - against the oracle's
+    max-subtracted fp64 softmax.  (2) List entries outside 0..i: they must contribute nothing."""
+    torch.manual_seed(7)
+    B, Hq, Hkv, T = 128, 4, 2, 1536
+    cu = [0, 1000, T]
+    q = torch.randn(T, Hq, 128) * 3.0
+    k = torch.randn(T, Hkv, 128)
+    v = torch.randn(T, Hkv, 128)
+    ramp = 1.0 + 6.0 * torch.arange(T).float() / T                     # later keys score higher
+    ramp[40::97] *= 3.0                                                # spikes inside blocks
+    k = k * ramp[:, None, None] + 0.5 * q.view(T, Hkv, 2, 128).mean(2) * ramp[:, None, None]
+    q, k, v = (x.to(torch.bfloat16) for x in (q, k, v))
+    qkv = tuple(x.float().numpy() for x in (q, k, v))
+    scale = 128 ** -0.5
+    logits = np.einsum("td,sd->ts", qkv[0][:, 0], qkv[1][:, 0]) * scale
+    assert np.abs(logits).max() > 200.0                                # e^200 overflows fp32
+    R, nbmax = so.total_rows(cu, B)
+    counts = np.zeros((Hq, R), np.int32)
+    idx = np.full((Hq, R, nbmax + 3), -1, np.int32)
+    clean_c, clean_i = counts.copy(), idx.copy()
+    r = np.random.default_rng(5)
+    for (_, _, nb, row0) in so.sequence_table(cu, B):
+        for i in range(nb):
+            for h in range(Hq):
+                pick = list(range(i + 1))
+                clean_c[h, row0 + i] = len(pick)
+                clean_i[h, row0 + i, :len(pick)] = pick
+                junk = [-3, i + 1 + int(r.integers(0, 50)), 2 ** 30][:int(r.integers(0, 4))]
+                dirty = pick[:len(pick) // 2] + junk[:1] + pick[len(pick) // 2:] + junk[1:]
+                counts[h, row0 + i] = len(dirty)
+                idx[h, row0 + i, :len(dirty)] = dirty
+    dev = torch.device("cuda:0")
+    qd, kd, vd = (x.to(dev) for x in (q, k, v))
+    shape = sb.Shape.from_tensors(qd, kd, B, cu)
+    o_out, o_lse = so.sparse_attention(*qkv, cu, B, clean_c, clean_i, scale)
+    for name, c, ix in (("clean", clean_c, clean_i), ("with unusable entries", counts, idx)):
+        out = torch.full_like(qd, float("nan"))
+        lse = torch.zeros((Hq, T), dtype=torch.float32, device=dev)
+        sb.stem_sparse_attn(shape, qd, kd, vd, torch.from_numpy(c).to(dev), torch.from_numpy(ix).to(dev),
+                            ix.shape[2], scale, out, lse)
+        torch.cuda.synchronize()
+        max_abs, rel_l2 = pu.check_output(out, o_out, name)
+        err = np.abs(lse.cpu().numpy() - o_lse) / np.maximum(1.0, np.abs(o_lse))
+        say("%s: max-abs %.4g rel-L2 %.4g, lse rel err %.3g" % (name, max_abs, rel_l2, err.max()))
+        assert err.max() <= 5e-3
+
+
 def test_outputs_are_deterministic_and_strided_views_work():
     """Same inputs twice give bit-identical results; Q/K/V given as views of a fused [T, H, d] QKV
     buffer (non-trivial token stride) give the same result as contiguous tensors."""
