@@ -204,10 +204,13 @@ def test_fused_estimate_select(name, ad_stride):
 
 
 @pytest.mark.parametrize("how", ["max", "mean"])
-@pytest.mark.parametrize("name", ["packed_b128", "ragged_b64"])
+@pytest.mark.parametrize("name", ["packed_b128", "ragged_b64", "odd_b64"])
 def test_group_shared_selection(name, how):
-    """One list per (KV head, row) from the group-reduced metric, used by all heads of the group."""
-    w = SMALL[name]
+    """One list per (KV head, row) from the group-reduced metric, used by all heads of the group.
+    odd_b64 has 15 x 15 scores per head, which the reduction cannot take four at a time."""
+    w = SMALL[name] if name in SMALL else wl.small("odd_b64", seed=27, num_q_heads=6, num_kv_heads=2,
+                                                    seq_lens=(15 * 64 - 3,), block_size=64, k_start=(5,),
+                                                    n_sink=1, n_local=1, outliers=(2,))
     G = w.num_q_heads // w.num_kv_heads
     say("case", w.name, "seed", w.seed, "group", how, "G", G)
     data = wl.generate(w)
@@ -307,13 +310,14 @@ def test_attention_on_given_lists_full_budget_and_random():
         assert np.abs(lse.cpu().numpy() - o_lse).max() <= 5e-3
 
 
-def test_attention_reference_moves_and_unusable_entries():
+@pytest.mark.parametrize("B", [128, 64])
+def test_attention_reference_moves_and_unusable_entries(B):
     """Two things ordinary data does not reach.  (1) Logits far outside the exponent range of a
     fixed reference, growing along the keys and jumping inside blocks, so that the softmax reference
     has to move at every check point of a block (and O is rescaled) - against the oracle's
     max-subtracted fp64 softmax.  (2) List entries outside 0..i: they must contribute nothing."""
     torch.manual_seed(7)
-    B, Hq, Hkv, T = 128, 4, 2, 1536
+    Hq, Hkv, T = 4, 2, 1536
     cu = [0, 1000, T]
     q = torch.randn(T, Hq, 128) * 3.0
     k = torch.randn(T, Hkv, 128)
@@ -352,6 +356,12 @@ def test_attention_reference_moves_and_unusable_entries():
                             ix.shape[2], scale, out, lse)
         torch.cuda.synchronize()
         max_abs, rel_l2 = pu.check_output(out, o_out, name)
+        if name == "clean":                                           # lse is optional: same output without it
+            out2 = torch.full_like(qd, float("nan"))
+            sb.stem_sparse_attn(shape, qd, kd, vd, torch.from_numpy(c).to(dev), torch.from_numpy(ix).to(dev),
+                                ix.shape[2], scale, out2, None)
+            torch.cuda.synchronize()
+            assert torch.equal(out, out2)
         err = np.abs(lse.cpu().numpy() - o_lse) / np.maximum(1.0, np.abs(o_lse))
         say("%s: max-abs %.4g rel-L2 %.4g, lse rel err %.3g" % (name, max_abs, rel_l2, err.max()))
         assert err.max() <= 5e-3
