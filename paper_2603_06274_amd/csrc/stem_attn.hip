@@ -341,6 +341,9 @@ __device__ __forceinline__ void sparse_attn_body(
 #pragma unroll
         for (int e = 0; e < 4; ++e) ps[e] = 0.f;
     };
+    // exp2-domain offset of the reference; a query that has seen nothing yet (m_ref = -inf) uses 0,
+    // which keeps its masked scores at exp2(-inf) = 0
+    auto reference_offset = [&]() { return m_ref == neg_inf ? 0.f : m_ref * sl2; };
     // Slow path for the window of pairs [q_lo, q_hi): take their true maximum, move the reference
     // up to it (rescaling O and l), and recompute the window's probabilities.
     auto fix_window = [&](int q_lo, int q_hi) {
@@ -363,19 +366,20 @@ __device__ __forceinline__ void sparse_attn_body(
 #pragma unroll
                 for (int x = 0; x < 16; ++x) o_acc[dt][x] *= corr;
         }
-        if (m_ref == neg_inf) m_ref = 0.f;             // nothing visible yet: any finite reference
-        off = m_ref * sl2;
+        off = reference_offset();
         clear_sum();
 #pragma unroll
         for (int q = q_lo; q < q_hi; ++q) softmax_pair(q);
     };
-    // a sum that is not a modest finite number (a probability above 2^16, inf, NaN) means the
-    // reference is too low for this window
-    auto overflowed = [&](float sum) { return __builtin_amdgcn_ballot_w64(!(sum <= 65536.0f)) != 0; };
-    bool first_block = true;
+    // A window needs the slow path if a query has no reference yet (nothing visible to it so far:
+    // every query on the first block) or if its sum is not a modest finite number (a probability
+    // above 2^16, inf, NaN: the reference is too low for this window).
+    auto needs_fix = [&](float sum) {
+        return __builtin_amdgcn_ballot_w64(m_ref == neg_inf || !(sum <= 65536.0f)) != 0;
+    };
     auto check_window = [&](int c) {                   // at slot boundary kCheckSlot[c]
         const int q_lo = c == 0 ? 0 : pairs_by(kCheckSlot[c - 1] - 1), q_hi = pairs_by(kCheckSlot[c] - 1);
-        if ((c == 0 && first_block) || overflowed(window_sum())) fix_window(q_lo, q_hi);
+        if (needs_fix(window_sum())) fix_window(q_lo, q_hi);
         l_run += window_sum();
         clear_sum();
     };
@@ -410,7 +414,7 @@ __device__ __forceinline__ void sparse_attn_body(
         for (int n = 0; n < kAhead; ++n) ka[n] = load_k(n);
         const auto v_rq = v_request(j);
         const int j_nxt = __builtin_amdgcn_readlane(list_reg, (it + 1) & 63);   // 0 past the end
-        off = m_ref * sl2;                             // -inf on the first block: redone at the first check
+        off = reference_offset();
         clear_sum();
         STEM_SCHED_FENCE();
 #pragma unroll
@@ -461,7 +465,6 @@ __device__ __forceinline__ void sparse_attn_body(
             }
         };
         check_window(0);
-        first_block = false;
         pv_range(0, kCheckSlot[1] - NS);
         check_window(1);
         if (kChecks == 3) {

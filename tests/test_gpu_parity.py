@@ -310,12 +310,15 @@ def test_attention_on_given_lists_full_budget_and_random():
         assert np.abs(lse.cpu().numpy() - o_lse).max() <= 5e-3
 
 
+@pytest.mark.parametrize("sign", [1.0, -1.0])
 @pytest.mark.parametrize("B", [128, 64])
-def test_attention_reference_moves_and_unusable_entries(B):
+def test_attention_reference_moves_and_unusable_entries(B, sign):
     """Two things ordinary data does not reach.  (1) Logits far outside the exponent range of a
     fixed reference, growing along the keys and jumping inside blocks, so that the softmax reference
     has to move at every check point of a block (and O is rescaled) - against the oracle's
-    max-subtracted fp64 softmax.  (2) List entries outside 0..i: they must contribute nothing."""
+    max-subtracted fp64 softmax; with sign = -1 every logit is hugely negative instead, so a
+    reference of zero would lose the row.  (2) List entries outside 0..i, also at the head of a
+    list: they must contribute nothing."""
     torch.manual_seed(7)
     Hq, Hkv, T = 4, 2, 1536
     cu = [0, 1000, T]
@@ -324,7 +327,7 @@ def test_attention_reference_moves_and_unusable_entries(B):
     v = torch.randn(T, Hkv, 128)
     ramp = 1.0 + 6.0 * torch.arange(T).float() / T                     # later keys score higher
     ramp[40::97] *= 3.0                                                # spikes inside blocks
-    k = k * ramp[:, None, None] + 0.5 * q.view(T, Hkv, 2, 128).mean(2) * ramp[:, None, None]
+    k = sign * (k * ramp[:, None, None] + 0.5 * q.view(T, Hkv, 2, 128).mean(2) * ramp[:, None, None])
     q, k, v = (x.to(torch.bfloat16) for x in (q, k, v))
     qkv = tuple(x.float().numpy() for x in (q, k, v))
     scale = 128 ** -0.5
@@ -342,7 +345,7 @@ def test_attention_reference_moves_and_unusable_entries(B):
                 clean_c[h, row0 + i] = len(pick)
                 clean_i[h, row0 + i, :len(pick)] = pick
                 junk = [-3, i + 1 + int(r.integers(0, 50)), 2 ** 30][:int(r.integers(0, 4))]
-                dirty = pick[:len(pick) // 2] + junk[:1] + pick[len(pick) // 2:] + junk[1:]
+                dirty = junk[2:] + pick[:len(pick) // 2] + junk[:1] + pick[len(pick) // 2:] + junk[1:2]
                 counts[h, row0 + i] = len(dirty)
                 idx[h, row0 + i, :len(dirty)] = dirty
     dev = torch.device("cuda:0")
