@@ -37,6 +37,9 @@ SMALL = {
     "batch64_b64": wl.small("batch64_b64", seed=26, num_q_heads=4, num_kv_heads=2,
                             seq_lens=tuple([0, 1, 64, 65, 300, 2] + [(37 * x) % 301 for x in range(58)]),
                             block_size=64, k_start=tuple([2] * 64), n_sink=1, n_local=1, outliers=tuple([1] * 64)),
+    # a start budget of zero: every row keeps exactly its forced windows
+    "forced_only_b128": wl.small("forced_only_b128", seed=28, num_q_heads=2, num_kv_heads=1, seq_lens=(2000, 300),
+                                 block_size=128, k_start=(0, 0), n_sink=2, n_local=3, outliers=(1, 1)),
     # no forced windows at all, uniform budget
     "noforce_b64": wl.small("noforce_b64", seed=25, num_q_heads=2, num_kv_heads=1, seq_lens=(2048, 1024),
                             block_size=64, k_start=(5, 3), n_sink=0, n_local=1, outliers=(2, 2), mu=1.0),
@@ -246,6 +249,32 @@ def test_group_shared_selection(name, how):
                               i_h[:, :, :min(indices.shape[2], i_h.shape[2])])
 
 
+def test_zero_blocks_in_the_inputs():
+    """A key block of zeros (scores reduce to the magnitude term), a value block of zeros (its
+    magnitude is ln 0 = -inf, clamped to 0 in the metric) and a query block of zeros (uniform
+    attention over what it selects)."""
+    w = wl.small("zeros_b64", seed=29, num_q_heads=4, num_kv_heads=2, seq_lens=(1024,), block_size=64,
+                 k_start=(5,), n_sink=1, n_local=1, outliers=(2,))
+    data = wl.generate(w)
+    data["k"][3 * 64:4 * 64] = 0
+    data["v"][5 * 64:6 * 64] = 0
+    data["q"][9 * 64:10 * 64] = 0
+    qkv = pu.host_arrays(data)
+    pf = pu.device_prefill(w, data)
+    pf.run()
+    torch.cuda.synchronize()
+    q_bar, k_bar, m_v, scores = pu.oracle_estimate(w, qkv)
+    assert np.isneginf(m_v[:, 5]).all()
+    pu.check_pooled(pf, q_bar, k_bar, m_v)
+    pu.check_scores(pf.scores.cpu().numpy(), scores)
+    _, counts, indices = pu.oracle_select(w, scores)
+    same = pu.check_lists(w, pf.counts.cpu().numpy(), pf.indices.cpu().numpy(), counts, indices, scores, say)
+    o_out, _ = so.sparse_attention(*qkv, w.cu_seqlens, w.block_size, counts, indices, w.softmax_scale)
+    for h, r in np.argwhere(~same):
+        o_out[r * 64:(r + 1) * 64, h] = np.nan
+    pu.check_output(pf.out, o_out, w.name)
+
+
 def test_select_is_bit_exact_on_shared_fp32_scores():
     """Stage 2 alone, on one fp32 score tensor given to both sides (exactly representable in fp64, so
     no near-tie allowance), with planted exact ties, +-0, and equal rows."""
@@ -272,6 +301,15 @@ def test_select_is_bit_exact_on_shared_fp32_scores():
         torch.cuda.synchronize()
         assert np.array_equal(counts.cpu().numpy(), want_c)
         assert np.array_equal(idx.cpu().numpy(), want_i[:, :, :kmax])
+        # a list pitch below the largest budget cuts the rows to it: the same as a clipped budget
+        cut = max(n_sink + n_local, kmax // 2)
+        want_c, want_i = so.select_blocks(sc.astype(np.float64), np.minimum(budget, cut), cu, B, n_sink, n_local)
+        idx_cut = torch.zeros((Hq, nb, cut), dtype=torch.int32, device=dev)
+        sb.stem_select(shape, torch.from_numpy(sc).to(dev), torch.from_numpy(budget).to(dev), n_sink, n_local,
+                       counts, idx_cut, cut)
+        torch.cuda.synchronize()
+        assert np.array_equal(counts.cpu().numpy(), want_c)
+        assert np.array_equal(idx_cut.cpu().numpy(), want_i[:, :, :cut])
 
 
 def test_attention_on_given_lists_full_budget_and_random():
