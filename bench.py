@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PAPER_H20_128K_DENSE_EQUIV_TFLOPS = 1.409e14 / 0.420 / 1e12   # dense-causal FLOPs of the layer / 420 ms
 
 # HBM-side bytes per sparse-attention launch on the 128K layer, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script (profiles/sparse_attn_kernel_llama8b_128k.md): FETCH_SIZE
@@ -93,7 +94,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     binding.lib()
-    w = workloads.BENCHMARK_CONFIGS[args.workload]
+    w = {**workloads.BENCHMARK_CONFIGS, **workloads.EXTRA_CONFIGS}[args.workload]
     data = workloads.generate(w)
     dev = torch.device("cuda:0")
     pf = StemPrefill(*(data[x].to(dev) for x in "qkv"), w.cu_seqlens, w.block_size, w.k_start_blocks, w.mu,
@@ -157,10 +158,15 @@ def main():
     pool_gbs = pool_bytes / (t_pool * 1e-3) / 1e9
 
     value = dense_flops / (ms_per_step * 1e-3) / 1e12
+    # The paper's only number for this path: 420 ms per 128K layer with its default schedule on an
+    # NVIDIA H20 (Empirical Latency), i.e. 335 dense-equivalent TFLOP/s for these shapes.  It applies
+    # to that schedule only and is another machine's figure: context, not a target.
+    vs_baseline = value / PAPER_H20_128K_DENSE_EQUIV_TFLOPS if w.name == "llama8b_128k_paper_preset" else None
     result = {
         "metric": "sparse prefill attention, dense-equivalent TFLOP/s at 128K (estimate + select + attention, one layer)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None if vs_baseline is None else round(vs_baseline, 2),
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "tokens": T, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d, "block": B,
                    "k_start_blocks": list(w.k_start_blocks), "mu": w.mu, "beta": w.beta,
