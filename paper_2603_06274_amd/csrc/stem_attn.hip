@@ -485,17 +485,29 @@ __device__ __forceinline__ void sparse_attn_body(
         l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
     }
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    // A lane holds four columns of every group of eight (the other four sit in lane ^ 32).  Two
+    // groups at a time, one half-wave swap per packed register gives each lane eight consecutive
+    // columns, i.e. 16-byte stores.  (The swap runs in every lane, valid query or not.)
+    uint4 packed[4][2];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int xa = m * 8, xb = m * 8 + 4;      // accumulators of groups 2m and 2m+1
+            const uint32_t a0 = pack_bf16(o_acc[dt][xa + 0] * inv, o_acc[dt][xa + 1] * inv);
+            const uint32_t a1 = pack_bf16(o_acc[dt][xa + 2] * inv, o_acc[dt][xa + 3] * inv);
+            const uint32_t b0 = pack_bf16(o_acc[dt][xb + 0] * inv, o_acc[dt][xb + 1] * inv);
+            const uint32_t b1 = pack_bf16(o_acc[dt][xb + 2] * inv, o_acc[dt][xb + 3] * inv);
+            const auto s0 = __builtin_amdgcn_permlane32_swap(a0, b0, false, false);
+            const auto s1 = __builtin_amdgcn_permlane32_swap(a1, b1, false, false);
+            packed[dt][m] = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+        }
     if (q_valid) {
-        uint16_t* dst = out + (int64_t)tok_q * q_st + (int64_t)h * q_sh + hi * 4;
+        uint16_t* dst = out + (int64_t)tok_q * q_st + (int64_t)h * q_sh + hi * 8;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int x4 = 0; x4 < 4; ++x4) {
-                uint2 pk;
-                pk.x = pack_bf16(o_acc[dt][x4 * 4 + 0] * inv, o_acc[dt][x4 * 4 + 1] * inv);
-                pk.y = pack_bf16(o_acc[dt][x4 * 4 + 2] * inv, o_acc[dt][x4 * 4 + 3] * inv);
-                *reinterpret_cast<uint2*>(dst + dt * 32 + x4 * 8) = pk;
-            }
+            for (int m = 0; m < 2; ++m) *reinterpret_cast<uint4*>(dst + dt * 32 + m * 16) = packed[dt][m];
         if (lse != nullptr && hi == 0)
             lse[(int64_t)h * T + tok_q] = l_tot > 0.f ? m_ref * scale + __logf(l_tot) : neg_inf;
     }
