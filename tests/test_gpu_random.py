@@ -31,3 +31,47 @@ def random_workload(seed: int) -> wl.Workload:
 @pytest.mark.parametrize("seed", range(24))
 def test_random_workload_whole_path(seed):
     run_both(random_workload(seed))
+
+
+@pytest.mark.parametrize("seed", range(24, 40))
+def test_random_workload_with_options(seed):
+    """The same with a random anti-diagonal stride, the fused stage 1-2 or group-shared lists."""
+    import torch
+    from oracle import stem_oracle as so
+    from paper_2603_06274_amd.prefill import StemPrefill
+    import parity_util as pu
+
+    w = random_workload(seed)
+    r = np.random.default_rng(5000 + seed)
+    S = int(r.choice([1, 2, 4, 8]))
+    group = [None, "max", "mean"][int(r.integers(0, 3))]
+    fused = group is None and bool(r.integers(0, 2))
+    print("case", w.name, "lens", w.seq_lens, "B", w.block_size, "S", S, "group", group, "fused", fused, flush=True)
+    data = wl.generate(w)
+    qkv = pu.host_arrays(data)
+    dev = torch.device("cuda:0")
+    q, k, v = (data[x].to(dev) for x in "qkv")
+    pf = StemPrefill(q, k, v, w.cu_seqlens, w.block_size, w.k_start_blocks, w.mu, w.k_min, w.n_sink, w.n_local,
+                     w.beta, w.route_scale, w.softmax_scale, want_lse=True, ad_stride=S, group_share=group)
+    pf.run(fused=fused)
+    torch.cuda.synchronize()
+    scores = pu.oracle_estimate(w, qkv, S)[3]
+    G = w.num_q_heads // w.num_kv_heads
+    if group:
+        scores = so.group_scores(scores, w.num_kv_heads, group)
+    _, counts, indices = pu.oracle_select(w, scores)
+    same = pu.check_lists(w, pf.counts.cpu().numpy(), pf.indices.cpu().numpy(), counts, indices, scores, print)
+    rep = G if group else 1
+    o_out, o_lse = so.sparse_attention(*qkv, w.cu_seqlens, w.block_size, np.repeat(counts, rep, axis=0),
+                                       np.repeat(indices, rep, axis=0), w.softmax_scale)
+    B = w.block_size
+    for (lo, hi, nb, row0) in so.sequence_table(w.cu_seqlens, B):
+        for i in range(nb):
+            for h in range(w.num_q_heads):
+                if not same[h // rep, row0 + i]:
+                    o_out[lo + i * B:min(lo + (i + 1) * B, hi), h] = np.nan
+                    o_lse[h, lo + i * B:min(lo + (i + 1) * B, hi)] = np.nan
+    pu.check_output(pf.out, o_out, w.name)
+    m = ~np.isnan(o_lse)
+    if m.any():
+        assert np.abs(pf.lse.cpu().numpy()[m] - o_lse[m]).max() <= 5e-3
