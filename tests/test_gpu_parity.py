@@ -122,7 +122,8 @@ def test_anti_diagonal_strides_estimate_and_select(name, ad_stride):
     say("%s S=%d: score err %.3g" % (w.name, ad_stride, err))
 
 
-def test_chunked_prefill_gives_the_rows_of_the_one_piece_call():
+@pytest.mark.parametrize("ad_stride,fused", [(1, False), (4, True)])
+def test_chunked_prefill_gives_the_rows_of_the_one_piece_call(ad_stride, fused):
     """A prompt processed in three chunks against its growing KV, with one workspace kept between
     the calls (each call pools only its own blocks): every chunk's scores, lists, outputs and lse
     are bit-identical to the matching rows of the one-piece call, whose parity with the oracle is
@@ -132,8 +133,14 @@ def test_chunked_prefill_gives_the_rows_of_the_one_piece_call():
     B, cu = w.block_size, list(w.cu_seqlens)
     data = wl.generate(w)
     qkv = pu.host_arrays(data)
-    full = pu.device_prefill(w, data)
-    full.run()
+    full = pu.device_prefill(w, data, ad_stride=ad_stride)
+    dump = torch.empty_like(full.scores) if fused else None
+    if fused:
+        full.estimate_select(dump)
+        full.scores.copy_(dump)
+        full.attend()
+    else:
+        full.run()
     torch.cuda.synchronize()
     dev = torch.device("cuda:0")
     q, k, v = (data[x].to(dev) for x in "qkv")
@@ -141,7 +148,7 @@ def test_chunked_prefill_gives_the_rows_of_the_one_piece_call():
     need = 0
     for starts, ends in calls:
         shape = sb.Shape.from_tensors(q, k, B, cu, (starts, ends))
-        need = max(need, sb.stem_workspace_bytes(shape, 1))
+        need = max(need, sb.stem_workspace_bytes(shape, ad_stride))
     ws = torch.full((need,), 0xFF, dtype=torch.uint8, device=dev)     # NaN patterns where nothing was pooled
     out = torch.zeros_like(full.out)
     full_row0 = [0, -(-(cu[1] - cu[0]) // B)]
@@ -149,8 +156,15 @@ def test_chunked_prefill_gives_the_rows_of_the_one_piece_call():
         say("chunk", starts, ends)
         qc = torch.cat([q[cu[s] + starts[s]:cu[s] + ends[s]] for s in range(2)]).contiguous()
         pf = StemPrefill(qc, k, v, cu, B, w.k_start_blocks, w.mu, w.k_min, w.n_sink, w.n_local, w.beta,
-                         w.route_scale, w.softmax_scale, want_lse=True, chunk=(starts, ends), workspace=ws)
-        pf.run()
+                         w.route_scale, w.softmax_scale, want_lse=True, chunk=(starts, ends), workspace=ws,
+                         ad_stride=ad_stride)
+        if fused:
+            chunk_dump = torch.empty_like(pf.scores)
+            pf.estimate_select(chunk_dump)
+            pf.scores.copy_(chunk_dump)
+            pf.attend()
+        else:
+            pf.run()
         torch.cuda.synchronize()
         r = t = 0
         for s in range(2):
@@ -172,7 +186,7 @@ def test_chunked_prefill_gives_the_rows_of_the_one_piece_call():
             t += n_tok
         assert r == pf.rows and t == qc.shape[0]
     # and the assembled chunks against the oracle's one-piece result
-    scores = pu.oracle_estimate(w, qkv)[3]
+    scores = pu.oracle_estimate(w, qkv, ad_stride)[3]
     _, counts, indices = pu.oracle_select(w, scores)
     same = pu.check_lists(w, full.counts.cpu().numpy(), full.indices.cpu().numpy(), counts, indices, scores, say)
     assert same.all()
