@@ -38,11 +38,22 @@ def median(xs):
     return xs[len(xs) // 2]
 
 
+def numpy_threads():
+    """Threads of the BLAS behind numpy (the oracle's matrix products are its only parallel part)."""
+    try:
+        from threadpoolctl import threadpool_info
+        blas = [p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"]
+        if blas:
+            return max(blas)
+    except Exception:
+        pass
+    return 1
+
+
 def cpu_baseline(w, data, dense_flops):
     """Times the oracle on KV group 0 (stages 1-2 in full, stage 3 on evenly spaced rows) and
     extrapolates to the layer."""
     import numpy as np
-    import torch
     from oracle import stem_oracle as so
 
     G = w.num_q_heads // w.num_kv_heads
@@ -65,7 +76,7 @@ def cpu_baseline(w, data, dense_flops):
     t_layer = w.num_kv_heads * (t12 + t3 * group_blocks / max(sampled_blocks, 1))
     return {
         "value": round(dense_flops / t_layer / 1e12, 4), "unit": "TFLOP/s (dense-equivalent)",
-        "cores": torch.get_num_threads(), "kind": "oracle",
+        "cores": numpy_threads(), "kind": "oracle",
         "sample": "KV group 0 (%d of %d query heads): stages 1-2 in full (%.1f s), stage 3 on %d of %d "
                   "query-block rows (%.1f s, %d listed blocks); layer time extrapolated by listed-block "
                   "count to %.0f s" % (G, w.num_q_heads, t12, n_rows, w.total_rows, t3, sampled_blocks, t_layer),
