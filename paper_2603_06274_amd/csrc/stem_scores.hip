@@ -4,10 +4,15 @@
 // (S = 1: the plain product of the two block means).
 //
 // A small fp32 contraction over S * d per head and sequence, lower-triangular in (i, j).  It is
-// kept in full fp32 FMA arithmetic (no bf16 matrix cores) because stage 2 ranks these numbers and
-// must reproduce the ranking of an fp64 evaluation except for genuine near-ties.  64 x 64 output
-// tiles, 4 x 4 per thread, operands staged k-major through LDS; tiles above the diagonal are only
-// filled with -inf.
+// kept in full fp32 arithmetic (no bf16 matrix cores) because stage 2 ranks these numbers and must
+// reproduce the ranking of an fp64 evaluation except for genuine near-ties: the products run on
+// the fp32 matrix instruction v_mfma_f32_32x32x2_f32.  64 x 64 output tiles, one 32 x 32 quadrant
+// per wave.  The operands go through LDS row-major exactly as they lie in memory (16-byte stores
+// of coalesced 16-byte loads); a lane then reads four consecutive depth positions of its row with
+// one 16-byte read and feeds them to four products.  Which depth position a product step pairs is
+// free as long as both operands agree, so step (u, x) takes position 8u + x from the lower half
+// of the wave and 8u + 4 + x from the upper half.  The loads of the next slice are in flight
+// during the products of the current one.  Tiles above the diagonal are only filled with -inf.
 #include "stem_common.h"
 
 namespace stem {
@@ -56,64 +61,77 @@ __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
         return;
     }
 
-    __shared__ float a_s[kChunk][kTile + 4];           // [k][i]
-    __shared__ float b_s[kChunk][kTile + 4];           // [k][j]
+    // [row][k] with rows 144 bytes apart: the 16-byte reads of 16 consecutive rows fall on 16
+    // different groups of four banks
+    // two buffers per operand: one barrier per slice
+    __shared__ __attribute__((aligned(16))) float a_s[2][kTile][kChunk + 4];
+    __shared__ __attribute__((aligned(16))) float b_s[2][kTile][kChunk + 4];
 
-    float acc[4][4];
+    typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+    f32x16_t acc;
 #pragma unroll
-    for (int x = 0; x < 4; ++x)
-#pragma unroll
-        for (int y = 0; y < 4; ++y) acc[x][y] = 0.f;
+    for (int x = 0; x < 16; ++x) acc[x] = 0.f;
+    const int lane = tid & 63, wv = tid >> 6;
+    const int col = lane & 31, hi = lane >> 5;
+    const int wi = (wv >> 1) * 32, wj = (wv & 1) * 32; // this wave's quadrant of the tile
 
     const int depth = S * kHeadDim;                    // floats per pooled block
     const float* a_src = q_bar + ((int64_t)h * R + row0) * depth;
     const float* b_src = k_bar + ((int64_t)g * Rk + krow0) * depth;
 
-    for (int kc = 0; kc < depth; kc += kChunk) {
-        // a chunk lies inside one residue class a of the query block; its partner is class S-1-a
+    // 64 rows x 32 floats per operand and slice = 512 float4: two per thread and operand
+    float4 av[2], bv[2];
+    auto fetch = [&](int kc) {
+        // a slice lies inside one residue class a of the query block; its partner is class S-1-a
         const int kb = (S - 1 - (kc >> 7)) * kHeadDim + (kc & (kHeadDim - 1));
-        // 64 rows x 32 floats per operand = 512 float4; two per thread and operand
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int idx = tid + kScoreThreads * u;
             const int row = idx >> 3, c4 = (idx & 7) * 4;
-            float4 av = make_float4(0.f, 0.f, 0.f, 0.f), bv = av;
-            if (i0 + row < n_rows) av = *reinterpret_cast<const float4*>(a_src + (int64_t)(i0 + row) * depth + kc + c4);
-            if (j0 + row < n) bv = *reinterpret_cast<const float4*>(b_src + (int64_t)(j0 + row) * depth + kb + c4);
-            a_s[c4 + 0][row] = av.x; a_s[c4 + 1][row] = av.y; a_s[c4 + 2][row] = av.z; a_s[c4 + 3][row] = av.w;
-            b_s[c4 + 0][row] = bv.x; b_s[c4 + 1][row] = bv.y; b_s[c4 + 2][row] = bv.z; b_s[c4 + 3][row] = bv.w;
+            av[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            bv[u] = av[u];
+            if (i0 + row < n_rows) av[u] = *reinterpret_cast<const float4*>(a_src + (int64_t)(i0 + row) * depth + kc + c4);
+            if (j0 + row < n) bv[u] = *reinterpret_cast<const float4*>(b_src + (int64_t)(j0 + row) * depth + kb + c4);
         }
-        __syncthreads();
+    };
+    auto stage = [&](int buf) {
 #pragma unroll
-        for (int kk = 0; kk < kChunk; ++kk) {
-            const float4 a4 = *reinterpret_cast<const float4*>(&a_s[kk][ti * 4]);
-            const float4 b4 = *reinterpret_cast<const float4*>(&b_s[kk][tj * 4]);
-            const float a[4] = {a4.x, a4.y, a4.z, a4.w};
-            const float b[4] = {b4.x, b4.y, b4.z, b4.w};
-#pragma unroll
-            for (int x = 0; x < 4; ++x)
-#pragma unroll
-                for (int y = 0; y < 4; ++y) acc[x][y] = fmaf(a[x], b[y], acc[x][y]);
+        for (int u = 0; u < 2; ++u) {
+            const int idx = tid + kScoreThreads * u;
+            const int row = idx >> 3, c4 = (idx & 7) * 4;
+            *reinterpret_cast<float4*>(&a_s[buf][row][c4]) = av[u];
+            *reinterpret_cast<float4*>(&b_s[buf][row][c4]) = bv[u];
         }
+    };
+    fetch(0);
+    stage(0);
+    __syncthreads();
+    int buf = 0;
+    for (int kc = 0; kc < depth; kc += kChunk, buf ^= 1) {
+        const bool more = kc + kChunk < depth;
+        if (more) fetch(kc + kChunk);
+#pragma unroll
+        for (int u = 0; u < kChunk / 8; ++u) {
+            const float4 a = *reinterpret_cast<const float4*>(&a_s[buf][wi + col][u * 8 + hi * 4]);
+            const float4 b = *reinterpret_cast<const float4*>(&b_s[buf][wj + col][u * 8 + hi * 4]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
+        }
+        // the other buffer was last read before the previous barrier
+        if (more) stage(buf ^ 1);
         __syncthreads();
     }
 
-    float mag[4];
+    // accumulator v of a lane: column wj + col, row wi + 8*(v/4) + 4*hi + v%4
+    const int j = j0 + wj + col;
+    const float mag = (j < n) ? beta * fmaxf(0.f, m_v[(int64_t)g * Rk + krow0 + j]) : 0.f;
 #pragma unroll
-    for (int y = 0; y < 4; ++y) {
-        const int j = j0 + tj * 4 + y;
-        mag[y] = (j < n) ? beta * fmaxf(0.f, m_v[(int64_t)g * Rk + krow0 + j]) : 0.f;
-    }
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-        const int i = i0 + ti * 4 + x;
-        if (i >= n_rows) continue;
-#pragma unroll
-        for (int y = 0; y < 4; ++y) {
-            const int j = j0 + tj * 4 + y;
-            if (j >= NBmax) continue;
-            out[(int64_t)i * NBmax + j] = (j <= first + i) ? fmaf(route_scale / (float)S, acc[x][y], mag[y]) : neg_inf;
-        }
+    for (int v = 0; v < 16; ++v) {
+        const int i = i0 + wi + 8 * (v >> 2) + 4 * hi + (v & 3);
+        if (i >= n_rows || j >= NBmax) continue;
+        out[(int64_t)i * NBmax + j] = (j <= first + i) ? fmaf(route_scale / (float)S, acc[v], mag) : neg_inf;
     }
 }
 
