@@ -2,7 +2,8 @@
 //
 // One 64-lane wavefront owns one (head, row).  The row's candidate scores are held in registers as
 // order-preserving 32-bit keys, lane-strided (element e of lane l is key block fs + 64 e + l).  The
-// k-th largest key is found exactly by a 32-step bitwise search whose counts come from wave ballots
+// k-th largest key is found exactly by a bitwise search (at most 32 steps; it stops as soon as a
+// prefix separates exactly the wanted number of keys) whose counts come from wave ballots
 // (scalar popcounts, no atomics, no LDS), and the list is then emitted in ascending block order by
 // ballot prefix compaction: forced blocks, every key above the threshold, and the lowest-indexed
 // keys equal to it until the budget is met.  The result is therefore deterministic and ties go to
@@ -46,17 +47,25 @@ __device__ __forceinline__ void select_row(Load load, int i, int row_budget, int
     uint32_t tau = 0;
     int n_eq = 0;                                      // keys equal to tau that are still needed
     if (need > 0 && need < nfree) {
-        for (int bit = 31; bit >= 0; --bit) {
+        bool exact = false;                            // exactly `need` keys are >= tau
+        for (int bit = 31; bit >= 0 && !exact; --bit) {
             const uint32_t cand = tau | (1u << bit);
             int cnt = 0;
 #pragma unroll
             for (int e = 0; e < ITEMS; ++e) cnt += __popcll(__ballot(key[e] >= cand));
             if (cnt >= need) tau = cand;
+            exact = cnt == need;
         }
-        int above = 0;
+        if (exact) {
+            // the keys >= tau are the answer whatever the remaining bits of the k-th largest key
+            // are: express it as "above tau - 1, none equal" (tau >= 1: a bit was just set)
+            tau -= 1;
+        } else {
+            int above = 0;
 #pragma unroll
-        for (int e = 0; e < ITEMS; ++e) above += __popcll(__ballot(key[e] > tau));
-        n_eq = need - above;
+            for (int e = 0; e < ITEMS; ++e) above += __popcll(__ballot(key[e] > tau));
+            n_eq = need - above;
+        }
     }
     const bool take_all = (need >= nfree);
 
@@ -124,13 +133,22 @@ int launch_select(const Problem& p, int heads, const float* scores, const int32_
 // Fused metric + selection: the scores of a band of query-block rows are computed into LDS and
 // selected from there, so the [Hq, R, NBmax] score tensor never exists in HBM.
 //
-// One workgroup owns (head h, band of ROWS consecutive rows of one sequence).  Phase 1 walks the
-// key blocks the band can see in chunks of 128: the chunk's pooled keys and the band's pooled
-// queries are staged through LDS 16 floats of the contraction at a time; wave w accumulates rows
-// 4w .. 4w+3 (ROWS = 16) or row w (ROWS = 4) of the band against the 128 keys, two adjacent keys
-// per lane, in fp32 FMAs (one 8-byte read of key values and one wave-wide broadcast of query
-// values per step).  Phase 2: every wave runs select_row on its rows with the scores read from LDS.
-// ROWS = 16 serves up to 1024 key blocks per row (16 x 1024 fp32 = 64 KiB of LDS), ROWS = 4 up to 4096.
+// One workgroup owns (head h, band of ROWS consecutive rows of one sequence).  Phase 1 fills
+// sc[row][key block] for the key blocks the band can see; phase 2: every wave runs select_row on
+// its rows with the scores read from LDS.  ROWS = 16 serves up to 1024 key blocks per row, ROWS = 4
+// up to 4096 (64 KiB of fp32 scores either way).
+//
+// Phase 1, ROWS = 16: the fp32 matrix instruction v_mfma_f32_16x16x4_f32 on tiles of 16 key blocks
+// x the band's 16 rows, operands loaded straight from the pooled workspace into registers (it is
+// L2-resident and every value is used once per tile, so LDS staging would only add traffic).  The
+// order in which the products walk the depth is free as long as both operands agree: lane
+// (r = lane % 16, c = lane / 16) holds, of its key block or row r, the floats 16u + 4c .. + 3 of
+// every 64-byte group u, so a 16-byte load serves four product steps and the four lanes of a row
+// read 64 contiguous bytes.  Wave w owns the tiles w, w + 4, ...; their accumulators (at most 16
+// tiles x 4 registers) stay in registers across the S residue classes, the next tile's keys are in
+// flight during the products of the current one.
+// Phase 1, ROWS = 4: fp32 FMAs on 128-key chunks staged through LDS 16 floats of the contraction at
+// a time; wave w accumulates row w against the 128 keys, two adjacent keys per lane.
 // ------------------------------------------------------------------------------------------------
 struct BandTable {
     int32_t band_start[STEM_MAX_BATCH + 1];            // prefix sums of ceil(rows of the call / ROWS)
@@ -138,9 +156,10 @@ struct BandTable {
 
 constexpr int kBandChunk = 16;                         // floats of the contraction staged per step
 constexpr int kBandKeys = 128;                         // key blocks per step
+constexpr int kScorePad = 4;                           // floats between rows of sc: 16-byte writes of 16 rows spread over all banks
 
 template <int ROWS>
-__global__ __launch_bounds__(256) void score_select_kernel(
+__global__ __launch_bounds__(256, 2) void score_select_kernel(
     const float* __restrict__ q_bar, const float* __restrict__ k_bar, const float* __restrict__ m_v,
     const int32_t* __restrict__ budget, int32_t* __restrict__ counts, int32_t* __restrict__ indices,
     float* __restrict__ debug_scores, SeqTable seq, BandTable bands, int R, int Rk, int NBmax, int G,
@@ -148,9 +167,7 @@ __global__ __launch_bounds__(256) void score_select_kernel(
     constexpr int NBcap = ROWS == 16 ? 1024 : 4096;    // key blocks per row held in LDS
     constexpr int RPW = ROWS / 4;                      // rows per wave
     constexpr int ITEMS = NBcap / 64;
-    __shared__ float sc[ROWS][NBcap];                  // 64 KiB
-    __shared__ __attribute__((aligned(16))) float ks[kBandChunk][kBandKeys + 2];   // [contraction][key]
-    __shared__ __attribute__((aligned(16))) float qs[kBandChunk][ROWS];            // [contraction][row]
+    __shared__ __attribute__((aligned(16))) float sc[ROWS][NBcap + kScorePad];
 
     // bands are handed out last first: within a sequence the later bands see more keys and take longer
     const int band = bands.band_start[seq.batch] - 1 - (int)blockIdx.x;
@@ -170,83 +187,153 @@ __global__ __launch_bounds__(256) void score_select_kernel(
 
     const float* a_src = q_bar + ((int64_t)h * R + row0 + ic0) * depth;
     const float* b_src = k_bar + ((int64_t)g * Rk + krow0) * depth;
+    const float* mag_src = m_v + (int64_t)g * Rk + krow0;
+    float* dbg = debug_scores != nullptr ? debug_scores + ((int64_t)h * R + row0 + ic0) * NBmax : nullptr;
+    int done;                                          // key blocks per row that phase 1 gives a value
 
-    // ---- phase 1: scores of the band into LDS.  The (key chunk, contraction slice) steps run as one
-    // sequence with the next step's global loads in flight while the current one is computed ----
-    const int slices = depth / kBandChunk;             // per key chunk
-    const int steps = (n_keys + kBandKeys - 1) / kBandKeys * slices;
-    float4 bv[2], av;
-    auto fetch = [&](int step) {
-        const int j0 = (step / slices) * kBandKeys, kc = (step % slices) * kBandChunk;
-        // a slice lies inside one residue class a of the query block; its partner is class S-1-a
-        const int kb = (S - 1 - (kc >> 7)) * kHeadDim + (kc & (kHeadDim - 1));
-        // keys: 128 rows x 16 floats = 512 float4, two per thread; queries: ROWS x 16 floats
+    if constexpr (ROWS == 16) {
+        typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+        constexpr int TPW = NBcap / 16 / 4;            // tiles per wave
+        const int r = lane & 15, c = lane >> 4;
+        const int n_tiles = (n_keys + 15) >> 4;
+        done = n_tiles * 16;
+        f32x4_t acc[TPW];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int idx = tid + 256 * u;
-            const int row = idx >> 2, c4 = (idx & 3) * 4;
-            bv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (j0 + row < n_keys) bv[u] = *reinterpret_cast<const float4*>(b_src + (int64_t)(j0 + row) * depth + kb + c4);
-        }
-        av = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (tid < ROWS * 4 && (tid >> 2) < band_rows)
-            av = *reinterpret_cast<const float4*>(a_src + (int64_t)(tid >> 2) * depth + kc + (tid & 3) * 4);
-    };
-    float acc[RPW][2];
+        for (int t = 0; t < TPW; ++t) acc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+        for (int a = 0; a < S; ++a) {
+            // the band's rows, residue class a; its partner among the keys is class S-1-a
+            float4 qv[8];
+            const float* q_row = a_src + (int64_t)r * depth + a * kHeadDim + 4 * c;
 #pragma unroll
-    for (int x = 0; x < RPW; ++x) acc[x][0] = acc[x][1] = 0.f;
-    if (steps > 0) fetch(0);
-    for (int step = 0; step < steps; ++step) {
+            for (int u = 0; u < 8; ++u)
+                qv[u] = (r < band_rows) ? *reinterpret_cast<const float4*>(q_row + 16 * u) : make_float4(0.f, 0.f, 0.f, 0.f);
+            const float* k_cls = b_src + (S - 1 - a) * kHeadDim + 4 * c;
+            float4 kv[8], kn[8];
+            auto load_keys = [&](float4* dst, int tile) {
+                const int j = tile * 16 + r;
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int idx = tid + 256 * u;
-            const int row = idx >> 2, c4 = (idx & 3) * 4;
-            ks[c4 + 0][row] = bv[u].x; ks[c4 + 1][row] = bv[u].y; ks[c4 + 2][row] = bv[u].z; ks[c4 + 3][row] = bv[u].w;
-        }
-        if (tid < ROWS * 4) {
-            const int row = tid >> 2, c4 = (tid & 3) * 4;
-            qs[c4 + 0][row] = av.x; qs[c4 + 1][row] = av.y; qs[c4 + 2][row] = av.z; qs[c4 + 3][row] = av.w;
-        }
-        __syncthreads();
-        if (step + 1 < steps) fetch(step + 1);
+                for (int u = 0; u < 8; ++u)
+                    dst[u] = (j < n_keys) ? *reinterpret_cast<const float4*>(k_cls + (int64_t)j * depth + 16 * u)
+                                          : make_float4(0.f, 0.f, 0.f, 0.f);
+            };
+            if (w < n_tiles) load_keys(kv, w);
 #pragma unroll
-        for (int kk = 0; kk < kBandChunk; ++kk) {
-            const float2 kv = *reinterpret_cast<const float2*>(&ks[kk][2 * lane]);
+            for (int t = 0; t < TPW; ++t) {
+                const int tile = 4 * t + w;
+                if (tile >= n_tiles) break;            // wave-uniform
+                if (tile + 4 < n_tiles) load_keys(kn, tile + 4);
 #pragma unroll
-            for (int x = 0; x < RPW; ++x) {
-                const float qv = qs[kk][w * RPW + x];
-                acc[x][0] = fmaf(qv, kv.x, acc[x][0]);
-                acc[x][1] = fmaf(qv, kv.y, acc[x][1]);
+                for (int u = 0; u < 8; ++u) {
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(kv[u].x, qv[u].x, acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(kv[u].y, qv[u].y, acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(kv[u].z, qv[u].z, acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(kv[u].w, qv[u].w, acc[t], 0, 0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) kv[u] = kn[u];
             }
         }
-        __syncthreads();
-        if (step % slices == slices - 1) {             // the chunk's contraction is complete
-            const int j0 = (step / slices) * kBandKeys;
+        // accumulator x of a lane: band row r, key block 16 tile + 4c + x
 #pragma unroll
-            for (int y = 0; y < 2; ++y) {
-                const int j = j0 + 2 * lane + y;
-                const float mag = (j < n_keys) ? beta * fmaxf(0.f, m_v[(int64_t)g * Rk + krow0 + j]) : 0.f;
+        for (int t = 0; t < TPW; ++t) {
+            const int tile = 4 * t + w;
+            if (tile >= n_tiles) break;
+            const int j0 = tile * 16 + 4 * c;
+            float val[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int j = j0 + x;
+                val[x] = neg_inf;
+                if (r < band_rows && j <= first + ic0 + r)   // implies j < n_keys
+                    val[x] = fmaf(route_scale / (float)S, acc[t][x], beta * fmaxf(0.f, mag_src[j]));
+            }
+            if (r >= band_rows) continue;
+            *reinterpret_cast<float4*>(&sc[r][j0]) = make_float4(val[0], val[1], val[2], val[3]);
+            if (dbg != nullptr) {
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    if (j0 + x < NBmax) dbg[(int64_t)r * NBmax + j0 + x] = val[x];
+            }
+        }
+    } else {
+        __shared__ __attribute__((aligned(16))) float ks[kBandChunk][kBandKeys + 2];   // [contraction][key]
+        __shared__ __attribute__((aligned(16))) float qs[kBandChunk][ROWS];            // [contraction][row]
+        // The (key chunk, contraction slice) steps run as one sequence with the next step's global
+        // loads in flight while the current one is computed.
+        const int slices = depth / kBandChunk;         // per key chunk
+        const int steps = (n_keys + kBandKeys - 1) / kBandKeys * slices;
+        done = (n_keys + kBandKeys - 1) / kBandKeys * kBandKeys;
+        float4 bv[2], av;
+        auto fetch = [&](int step) {
+            const int j0 = (step / slices) * kBandKeys, kc = (step % slices) * kBandChunk;
+            // a slice lies inside one residue class a of the query block; its partner is class S-1-a
+            const int kb = (S - 1 - (kc >> 7)) * kHeadDim + (kc & (kHeadDim - 1));
+            // keys: 128 rows x 16 floats = 512 float4, two per thread; queries: ROWS x 16 floats
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int idx = tid + 256 * u;
+                const int row = idx >> 2, c4 = (idx & 3) * 4;
+                bv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (j0 + row < n_keys) bv[u] = *reinterpret_cast<const float4*>(b_src + (int64_t)(j0 + row) * depth + kb + c4);
+            }
+            av = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (tid < ROWS * 4 && (tid >> 2) < band_rows)
+                av = *reinterpret_cast<const float4*>(a_src + (int64_t)(tid >> 2) * depth + kc + (tid & 3) * 4);
+        };
+        float acc[RPW][2];
+#pragma unroll
+        for (int x = 0; x < RPW; ++x) acc[x][0] = acc[x][1] = 0.f;
+        if (steps > 0) fetch(0);
+        for (int step = 0; step < steps; ++step) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int idx = tid + 256 * u;
+                const int row = idx >> 2, c4 = (idx & 3) * 4;
+                ks[c4 + 0][row] = bv[u].x; ks[c4 + 1][row] = bv[u].y; ks[c4 + 2][row] = bv[u].z; ks[c4 + 3][row] = bv[u].w;
+            }
+            if (tid < ROWS * 4) {
+                const int row = tid >> 2, c4 = (tid & 3) * 4;
+                qs[c4 + 0][row] = av.x; qs[c4 + 1][row] = av.y; qs[c4 + 2][row] = av.z; qs[c4 + 3][row] = av.w;
+            }
+            __syncthreads();
+            if (step + 1 < steps) fetch(step + 1);
+#pragma unroll
+            for (int kk = 0; kk < kBandChunk; ++kk) {
+                const float2 kv = *reinterpret_cast<const float2*>(&ks[kk][2 * lane]);
 #pragma unroll
                 for (int x = 0; x < RPW; ++x) {
-                    const int row = w * RPW + x;
-                    const float val = (j <= first + ic0 + row) ? fmaf(route_scale / (float)S, acc[x][y], mag) : neg_inf;
-                    acc[x][y] = 0.f;
-                    if (row >= band_rows || j >= NBcap) continue;
-                    sc[row][j] = val;
-                    if (debug_scores != nullptr && j < NBmax)
-                        debug_scores[((int64_t)h * R + row0 + ic0 + row) * NBmax + j] = val;
+                    const float qv = qs[kk][w * RPW + x];
+                    acc[x][0] = fmaf(qv, kv.x, acc[x][0]);
+                    acc[x][1] = fmaf(qv, kv.y, acc[x][1]);
+                }
+            }
+            __syncthreads();
+            if (step % slices == slices - 1) {         // the chunk's contraction is complete
+                const int j0 = (step / slices) * kBandKeys;
+#pragma unroll
+                for (int y = 0; y < 2; ++y) {
+                    const int j = j0 + 2 * lane + y;
+                    const float mag = (j < n_keys) ? beta * fmaxf(0.f, mag_src[j]) : 0.f;
+#pragma unroll
+                    for (int x = 0; x < RPW; ++x) {
+                        const int row = w * RPW + x;
+                        const float val = (j <= first + ic0 + row) ? fmaf(route_scale / (float)S, acc[x][y], mag) : neg_inf;
+                        acc[x][y] = 0.f;
+                        if (row >= band_rows || j >= NBcap) continue;
+                        sc[row][j] = val;
+                        if (dbg != nullptr && j < NBmax) dbg[(int64_t)row * NBmax + j] = val;
+                    }
                 }
             }
         }
     }
     // the rest of a debug row is -inf, as in the unfused score tensor
-    if (debug_scores != nullptr) {
-        const int done = (n_keys + kBandKeys - 1) / kBandKeys * kBandKeys;
+    if (dbg != nullptr) {
         for (int x = 0; x < RPW; ++x) {
             const int row = w * RPW + x;
             if (row >= band_rows) continue;
-            for (int j = done + lane; j < NBmax; j += 64)
-                debug_scores[((int64_t)h * R + row0 + ic0 + row) * NBmax + j] = neg_inf;
+            for (int j = done + lane; j < NBmax; j += 64) dbg[(int64_t)row * NBmax + j] = neg_inf;
         }
     }
     __syncthreads();
