@@ -36,8 +36,9 @@
  *     sequence for the schedule, the causal limit and the windows, so the chunks of a prompt give
  *     the rows of the one-piece call.  chunk_start must be a multiple of B, chunk_end a multiple
  *     of B or the sequence's length; an empty chunk (start == end) contributes nothing.
- *   - Supported: head_dim 128; block_size 64 or 128; 1 <= batch <= STEM_MAX_BATCH; Hq a multiple
- *     of Hkv; at most STEM_MAX_BLOCKS blocks per sequence.
+ *   - Supported: head_dim 64, 128 or 256 (the attention kernel tuned for this GPU is the one for
+ *     128; the other two sizes run a plainer kernel of the same arithmetic); block_size 64 or 128;
+ *     1 <= batch <= STEM_MAX_BATCH; Hq a multiple of Hkv; at most STEM_MAX_BLOCKS blocks per sequence.
  */
 #ifndef STEM_H
 #define STEM_H
@@ -61,7 +62,7 @@ extern "C" {
 typedef struct stem_shape {
     int32_t num_q_heads;             /* Hq                                                          */
     int32_t num_kv_heads;            /* Hkv, divides Hq                                             */
-    int32_t head_dim;                /* d = 128                                                     */
+    int32_t head_dim;                /* d = 64, 128 or 256                                          */
     int32_t block_size;              /* B = 64 or 128 (the paper fixes 128)                         */
     int32_t batch;                   /* number of packed sequences                                  */
     const int32_t* host_cu_seqlens;  /* HOST [batch+1], cu[0] = 0, non-decreasing; read during call */

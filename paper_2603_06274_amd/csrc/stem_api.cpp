@@ -15,10 +15,10 @@ int make_problem(const stem_shape* s, Problem* out) {
         return STEM_ERR_INVALID_ARG;
     if (s->batch < 1 || s->batch > STEM_MAX_BATCH) return STEM_ERR_INVALID_ARG;
     if (s->head_dim <= 0 || s->block_size <= 0) return STEM_ERR_INVALID_ARG;
-    if (s->head_dim != kHeadDim) return STEM_ERR_UNSUPPORTED;
+    if (s->head_dim != 64 && s->head_dim != 128 && s->head_dim != 256) return STEM_ERR_UNSUPPORTED;
     if (s->block_size != 64 && s->block_size != 128) return STEM_ERR_UNSUPPORTED;
-    if (s->q_stride_head < kHeadDim || s->kv_stride_head < kHeadDim) return STEM_ERR_INVALID_ARG;
-    if (s->q_stride_token < kHeadDim || s->kv_stride_token < kHeadDim) return STEM_ERR_INVALID_ARG;
+    if (s->q_stride_head < s->head_dim || s->kv_stride_head < s->head_dim) return STEM_ERR_INVALID_ARG;
+    if (s->q_stride_token < s->head_dim || s->kv_stride_token < s->head_dim) return STEM_ERR_INVALID_ARG;
     if ((s->q_stride_head | s->q_stride_token | s->kv_stride_head | s->kv_stride_token) & 7)
         return STEM_ERR_INVALID_ARG;
     Problem p;
@@ -27,6 +27,7 @@ int make_problem(const stem_shape* s, Problem* out) {
     p.Hkv = s->num_kv_heads;
     p.G = p.Hq / p.Hkv;
     p.B = s->block_size;
+    p.d = s->head_dim;
     p.batch = s->batch;
     p.q_st = s->q_stride_token;
     p.q_sh = s->q_stride_head;
@@ -95,9 +96,9 @@ WorkspaceLayout workspace_layout(const Problem& p, int ad_stride) {
     // the key parts come first and depend on the sequences only, not on the chunk: a caller that
     // keeps the workspace between the chunks of a prompt finds the earlier chunks' keys in place
     w.k_bar = 0;
-    w.m_v = align256(w.k_bar + sizeof(float) * (size_t)p.Hkv * p.Rk * ad_stride * kHeadDim);
+    w.m_v = align256(w.k_bar + sizeof(float) * (size_t)p.Hkv * p.Rk * ad_stride * p.d);
     w.q_bar = align256(w.m_v + sizeof(float) * (size_t)p.Hkv * p.Rk);
-    w.total = align256(w.q_bar + sizeof(float) * (size_t)p.Hq * p.R * ad_stride * kHeadDim);
+    w.total = align256(w.q_bar + sizeof(float) * (size_t)p.Hq * p.R * ad_stride * p.d);
     if (w.total == 0) w.total = 256;
     return w;
 }
@@ -108,7 +109,7 @@ using namespace stem;
 
 extern "C" {
 
-int stem_version(void) { return 200; }
+int stem_version(void) { return 300; }
 
 const char* stem_strerror(int status) {
     switch (status) {

@@ -32,6 +32,8 @@
 
 namespace stem {
 
+constexpr int kHeadDim = 128;                          // the head size this kernel is built for
+
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
@@ -530,6 +532,9 @@ int launch_sparse_attn(const Problem& p, const void* q, const void* k, const voi
                        const int32_t* counts, const int32_t* indices, int32_t kmax,
                        bool lists_per_kv_head, float softmax_scale, void* out, float* lse,
                        hipStream_t stream) {
+    if (p.d != kHeadDim)
+        return launch_sparse_attn_generic(p, q, k, v, counts, indices, kmax, lists_per_kv_head, softmax_scale,
+                                          out, lse, stream);
     // the block requests address one sequence of one KV head through a 32-bit byte offset, with
     // offsets from 2^31 on reserved for requests that must fetch nothing
     for (int s = 0; s < p.batch; ++s) {

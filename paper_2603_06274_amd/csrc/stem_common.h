@@ -8,8 +8,6 @@
 
 namespace stem {
 
-constexpr int kHeadDim = 128;
-
 // Packed-sequence table, passed to kernels by value (no device-side cu_seqlens read, no sync).
 // A call covers, of every sequence, the query blocks of one chunk [chunk_start, chunk_end) (the
 // whole sequence unless the shape says otherwise) and the keys before chunk_end.
@@ -26,6 +24,7 @@ struct SeqTable {
 // Everything the host derives from a stem_shape.
 struct Problem {
     int32_t Hq, Hkv, G, B, batch;
+    int32_t d;        // head size: 64, 128 or 256
     int32_t T;        // query tokens of the call (rows of Q, O, lse)
     int32_t R;        // query-block rows of the call
     int32_t Rk;       // blocks of all sequences (rows of k_bar, m_v)
@@ -59,10 +58,15 @@ int launch_score_select(const Problem& p, int ad_stride, const float* q_bar, con
                         const float* m_v, float beta, float route_scale, const int32_t* budget,
                         int32_t n_sink, int32_t n_local, int32_t* counts, int32_t* indices,
                         int32_t kmax, float* debug_scores, hipStream_t stream);
+// head size 128 runs the tuned kernel, 64 and 256 go on to launch_sparse_attn_generic
 int launch_sparse_attn(const Problem& p, const void* q, const void* k, const void* v,
                        const int32_t* counts, const int32_t* indices, int32_t kmax,
                        bool lists_per_kv_head, float softmax_scale, void* out, float* lse,
                        hipStream_t stream);
+int launch_sparse_attn_generic(const Problem& p, const void* q, const void* k, const void* v,
+                               const int32_t* counts, const int32_t* indices, int32_t kmax,
+                               bool lists_per_kv_head, float softmax_scale, void* out, float* lse,
+                               hipStream_t stream);
 
 inline int check_launch() {
     return hipGetLastError() == hipSuccess ? STEM_OK : STEM_ERR_HIP;

@@ -1,10 +1,11 @@
 // Stage 1a (Algorithm 1 step 1): block-wise pooling of Q and K and max-pooled value magnitude.
 //
 // Pure HBM stream: every bf16 element of Q, K and V is read exactly once, in 16-byte lane loads
-// that cover one head row (256 B) per 16 lanes.  One workgroup owns one (row, tensor, head) slot:
-// 256 threads = 16 token lanes x 16 column chunks; every thread issues all of its loads (B/16
-// tokens) before it touches the first value, so a workgroup keeps B x 256 B in flight.  Column
-// sums are reduced across the 16 token lanes through LDS in a fixed order (deterministic fp32).
+// that cover one head row (2 d bytes) per d / 8 lanes.  One workgroup owns one (row, tensor, head)
+// slot: 2 d threads = 16 token lanes x d / 8 column chunks (256 threads at d = 128); every thread
+// issues all of its loads (B/16 tokens) before it touches the first value, so a workgroup keeps
+// the whole B x 2 d bytes in flight.  Column sums are reduced across the 16 token lanes through
+// LDS in a fixed order (deterministic fp32).
 //
 // With an anti-diagonal stride S > 1 (S divides 16) a block keeps S partial means, one per residue
 // class of the in-block token position modulo S.  A thread's tokens tl, tl + 16, ... all fall in
@@ -14,8 +15,6 @@
 
 namespace stem {
 
-constexpr int kPoolThreads = 256;
-
 // 16-byte load marked non-temporal: the stream is read once here, and a read that does not claim
 // cache lines runs measurably closer to the HBM rate (7.0 against 6.3 TB/s for a bare read).
 __device__ __forceinline__ uint4 load_streaming(const uint16_t* p) {
@@ -24,12 +23,14 @@ __device__ __forceinline__ uint4 load_streaming(const uint16_t* p) {
     return make_uint4(x.x, x.y, x.z, x.w);
 }
 
-template <int B>
-__global__ __launch_bounds__(kPoolThreads) void pool_kernel(
+template <int B, int D>
+__global__ __launch_bounds__(2 * D) void pool_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     float* __restrict__ q_bar, float* __restrict__ k_bar, float* __restrict__ m_v, SeqTable seq,
     int Hq, int Hkv, int R, int Rk, int S, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh) {
     constexpr int kTok = B / 16;                       // tokens per thread
+    constexpr int kThreads = 2 * D;
+    constexpr int kChunks = D / 8;                     // 16-byte chunks per row: 8, 16 or 32
     const int slots = Hq + 2 * Hkv;
     const int r = blockIdx.x / slots;
     const int slot = blockIdx.x - r * slots;
@@ -53,8 +54,8 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
     }
 
     const int tid = threadIdx.x;
-    const int c = tid & 15;                            // 16-byte chunk of the 128-wide row
-    const int tl = tid >> 4;                           // token lane 0..15
+    const int c = tid % kChunks;                       // 16-byte chunk of the row
+    const int tl = tid / kChunks;                      // token lane 0..15
 
     uint4 raw[kTok];
 #pragma unroll
@@ -64,8 +65,8 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
         if (t < n_valid) raw[u] = load_streaming(src + (int64_t)(tok0 + t) * st + c * 8);
     }
 
-    __shared__ float part[16][kHeadDim + 4];           // [token lane][column]
-    __shared__ float vmax[kPoolThreads / 64];
+    __shared__ float part[16][D + 4];                  // [token lane][column]
+    __shared__ float vmax[kThreads / 64];
 
     if (kind != 2) {
         float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -79,17 +80,17 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) part[tl][c * 8 + e] = acc[e];
         __syncthreads();
-        float* dst = kind == 0 ? q_bar + ((int64_t)head * R + r) * S * kHeadDim
-                               : k_bar + ((int64_t)head * Rk + key_row) * S * kHeadDim;
-        for (int o = tid; o < S * kHeadDim; o += kPoolThreads) {
-            const int a = o >> 7, col = o & (kHeadDim - 1);   // residue class, column
+        float* dst = kind == 0 ? q_bar + ((int64_t)head * R + r) * S * D
+                               : k_bar + ((int64_t)head * Rk + key_row) * S * D;
+        for (int o = tid; o < S * D; o += kThreads) {
+            const int a = o / D, col = o % D;          // residue class, column
             float sum = 0.f;
             for (int x = a; x < 16; x += S) sum += part[x][col];
             const int members = (n_valid - a + S - 1) / S;    // valid tokens of the class (n_valid > a)
             dst[o] = n_valid > a ? sum / (float)members : 0.f;
         }
     } else {
-        // squared L2 norm of each token row: 8 columns per lane, then across the 16 chunk lanes
+        // squared L2 norm of each token row: 8 columns per lane, then across the row's chunk lanes
         float best = 0.f;
 #pragma unroll
         for (int u = 0; u < kTok; ++u) {
@@ -98,18 +99,18 @@ __global__ __launch_bounds__(kPoolThreads) void pool_kernel(
                   x6 = bf16_lo(raw[u].w), x7 = bf16_hi(raw[u].w);
             float ss = ((x0 * x0 + x1 * x1) + (x2 * x2 + x3 * x3)) +
                        ((x4 * x4 + x5 * x5) + (x6 * x6 + x7 * x7));
-            ss += __shfl_xor(ss, 1);
-            ss += __shfl_xor(ss, 2);
-            ss += __shfl_xor(ss, 4);
-            ss += __shfl_xor(ss, 8);
+#pragma unroll
+            for (int x = 1; x < kChunks; x *= 2) ss += __shfl_xor(ss, x);
             best = fmaxf(best, ss);                    // padded tokens contribute 0
         }
-        best = fmaxf(best, __shfl_xor(best, 16));
-        best = fmaxf(best, __shfl_xor(best, 32));
+#pragma unroll
+        for (int x = kChunks; x < 64; x *= 2) best = fmaxf(best, __shfl_xor(best, x));
         if ((tid & 63) == 0) vmax[tid >> 6] = best;
         __syncthreads();
         if (tid == 0) {
-            float m = fmaxf(fmaxf(vmax[0], vmax[1]), fmaxf(vmax[2], vmax[3]));
+            float m = vmax[0];
+#pragma unroll
+            for (int x = 1; x < kThreads / 64; ++x) m = fmaxf(m, vmax[x]);
             // max_t ln ||v_t|| = 0.5 ln max_t ||v_t||^2 ; ln 0 = -inf
             m_v[(int64_t)head * Rk + key_row] = 0.5f * logf(m);
         }
@@ -121,16 +122,21 @@ int launch_pool(const Problem& p, int ad_stride, const void* q, const void* k, c
     if (ad_stride < 1 || 16 % ad_stride) return STEM_ERR_UNSUPPORTED;
     const int64_t blocks = (int64_t)p.R * (p.Hq + 2 * p.Hkv);
     if (blocks > 0x7fffffff) return STEM_ERR_UNSUPPORTED;
-    dim3 grid((unsigned)blocks), block(kPoolThreads);
+    dim3 grid((unsigned)blocks), block(2 * p.d);
     const uint16_t* qq = static_cast<const uint16_t*>(q);
     const uint16_t* kk = static_cast<const uint16_t*>(k);
     const uint16_t* vv = static_cast<const uint16_t*>(v);
-    if (p.B == 128)
-        hipLaunchKernelGGL(pool_kernel<128>, grid, block, 0, stream, qq, kk, vv, q_bar, k_bar, m_v,
-                           p.seq, p.Hq, p.Hkv, p.R, p.Rk, ad_stride, p.q_st, p.q_sh, p.kv_st, p.kv_sh);
-    else
-        hipLaunchKernelGGL(pool_kernel<64>, grid, block, 0, stream, qq, kk, vv, q_bar, k_bar, m_v,
-                           p.seq, p.Hq, p.Hkv, p.R, p.Rk, ad_stride, p.q_st, p.q_sh, p.kv_st, p.kv_sh);
+#define STEM_POOL_LAUNCH(BB, DD)                                                                   \
+    hipLaunchKernelGGL((pool_kernel<BB, DD>), grid, block, 0, stream, qq, kk, vv, q_bar, k_bar,    \
+                       m_v, p.seq, p.Hq, p.Hkv, p.R, p.Rk, ad_stride, p.q_st, p.q_sh, p.kv_st, p.kv_sh)
+    if (p.B == 128 && p.d == 128) STEM_POOL_LAUNCH(128, 128);
+    else if (p.B == 64 && p.d == 128) STEM_POOL_LAUNCH(64, 128);
+    else if (p.B == 128 && p.d == 64) STEM_POOL_LAUNCH(128, 64);
+    else if (p.B == 64 && p.d == 64) STEM_POOL_LAUNCH(64, 64);
+    else if (p.B == 128 && p.d == 256) STEM_POOL_LAUNCH(128, 256);
+    else if (p.B == 64 && p.d == 256) STEM_POOL_LAUNCH(64, 256);
+    else return STEM_ERR_UNSUPPORTED;
+#undef STEM_POOL_LAUNCH
     return check_launch();
 }
 

@@ -28,7 +28,7 @@ struct TileTable {
 __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
     const float* __restrict__ q_bar, const float* __restrict__ k_bar, const float* __restrict__ m_v,
     float* __restrict__ scores, SeqTable seq, TileTable tiles, int R, int Rk, int NBmax, int G, int S,
-    float beta, float route_scale) {
+    int d_log2, float beta, float route_scale) {
     // sequence and local row tile of this workgroup
     int s = 0;
     for (int x = 1; x < seq.batch; ++x) s = ((int)blockIdx.x >= tiles.tile_start[x]) ? x : s;
@@ -75,7 +75,8 @@ __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
     const int col = lane & 31, hi = lane >> 5;
     const int wi = (wv >> 1) * 32, wj = (wv & 1) * 32; // this wave's quadrant of the tile
 
-    const int depth = S * kHeadDim;                    // floats per pooled block
+    const int d = 1 << d_log2;
+    const int depth = S * d;                           // floats per pooled block
     const float* a_src = q_bar + ((int64_t)h * R + row0) * depth;
     const float* b_src = k_bar + ((int64_t)g * Rk + krow0) * depth;
 
@@ -83,7 +84,7 @@ __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
     float4 av[2], bv[2];
     auto fetch = [&](int kc) {
         // a slice lies inside one residue class a of the query block; its partner is class S-1-a
-        const int kb = (S - 1 - (kc >> 7)) * kHeadDim + (kc & (kHeadDim - 1));
+        const int kb = (S - 1 - (kc >> d_log2)) * d + (kc & (d - 1));
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int idx = tid + kScoreThreads * u;
@@ -148,7 +149,7 @@ int launch_block_scores(const Problem& p, int ad_stride, const float* q_bar, con
     if (p.Hq > 65535) return STEM_ERR_UNSUPPORTED;
     dim3 grid(total, (p.NBmax + kTile - 1) / kTile, p.Hq), block(kScoreThreads);
     hipLaunchKernelGGL(block_scores_kernel, grid, block, 0, stream, q_bar, k_bar, m_v, scores, p.seq,
-                       tiles, p.R, p.Rk, p.NBmax, p.G, ad_stride, beta, route_scale);
+                       tiles, p.R, p.Rk, p.NBmax, p.G, ad_stride, __builtin_ctz(p.d), beta, route_scale);
     return check_launch();
 }
 

@@ -145,8 +145,8 @@ int launch_select(const Problem& p, int heads, const float* scores, const int32_
 // (r = lane % 16, c = lane / 16) holds, of its key block or row r, the floats 16u + 4c .. + 3 of
 // every 64-byte group u, so a 16-byte load serves four product steps and the four lanes of a row
 // read 64 contiguous bytes.  Wave w owns the tiles w, w + 4, ...; their accumulators (at most 16
-// tiles x 4 registers) stay in registers across the S residue classes, the next tile's keys are in
-// flight during the products of the current one.
+// tiles x 4 registers) stay in registers across the whole depth, which is walked 64 floats at a
+// time; the next tile's keys are in flight during the products of the current one.
 // Phase 1, ROWS = 4: fp32 FMAs on 128-key chunks staged through LDS 16 floats of the contraction at
 // a time; wave w accumulates row w against the 128 keys, two adjacent keys per lane.
 // ------------------------------------------------------------------------------------------------
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256, 2) void score_select_kernel(
     const float* __restrict__ q_bar, const float* __restrict__ k_bar, const float* __restrict__ m_v,
     const int32_t* __restrict__ budget, int32_t* __restrict__ counts, int32_t* __restrict__ indices,
     float* __restrict__ debug_scores, SeqTable seq, BandTable bands, int R, int Rk, int NBmax, int G,
-    int S, float beta, float route_scale, int n_sink, int n_local, int kmax) {
+    int S, int d_log2, float beta, float route_scale, int n_sink, int n_local, int kmax) {
     constexpr int NBcap = ROWS == 16 ? 1024 : 4096;    // key blocks per row held in LDS
     constexpr int RPW = ROWS / 4;                      // rows per wave
     constexpr int ITEMS = NBcap / 64;
@@ -182,7 +182,8 @@ __global__ __launch_bounds__(256, 2) void score_select_kernel(
     const int n_keys = first + ic0 + band_rows;        // key blocks the band's last row can see
     const int h = blockIdx.y, g = h / G;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int depth = S * kHeadDim;
+    const int d = 1 << d_log2;
+    const int depth = S * d;
     const float neg_inf = -__builtin_huge_valf();
 
     const float* a_src = q_bar + ((int64_t)h * R + row0 + ic0) * depth;
@@ -201,19 +202,22 @@ __global__ __launch_bounds__(256, 2) void score_select_kernel(
 #pragma unroll
         for (int t = 0; t < TPW; ++t) acc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-        for (int a = 0; a < S; ++a) {
-            // the band's rows, residue class a; its partner among the keys is class S-1-a
-            float4 qv[8];
-            const float* q_row = a_src + (int64_t)r * depth + a * kHeadDim + 4 * c;
+        // The contraction runs over S * d / 64 segments of 64 floats, each inside one residue class
+        // a of the query block; its partner among the keys is the same columns of class S-1-a.
+        const int segs_per_class = d >> 6;
+        for (int seg = 0; seg < S * segs_per_class; ++seg) {
+            const int a = seg / segs_per_class, col0 = (seg - a * segs_per_class) * 64 + 4 * c;
+            float4 qv[4];
+            const float* q_row = a_src + (int64_t)r * depth + a * d + col0;
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < 4; ++u)
                 qv[u] = (r < band_rows) ? *reinterpret_cast<const float4*>(q_row + 16 * u) : make_float4(0.f, 0.f, 0.f, 0.f);
-            const float* k_cls = b_src + (S - 1 - a) * kHeadDim + 4 * c;
-            float4 kv[8], kn[8];
+            const float* k_cls = b_src + (S - 1 - a) * d + col0;
+            float4 kv[4], kn[4];
             auto load_keys = [&](float4* dst, int tile) {
                 const int j = tile * 16 + r;
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
+                for (int u = 0; u < 4; ++u)
                     dst[u] = (j < n_keys) ? *reinterpret_cast<const float4*>(k_cls + (int64_t)j * depth + 16 * u)
                                           : make_float4(0.f, 0.f, 0.f, 0.f);
             };
@@ -224,14 +228,14 @@ __global__ __launch_bounds__(256, 2) void score_select_kernel(
                 if (tile >= n_tiles) break;            // wave-uniform
                 if (tile + 4 < n_tiles) load_keys(kn, tile + 4);
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < 4; ++u) {
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(kv[u].x, qv[u].x, acc[t], 0, 0, 0);
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(kv[u].y, qv[u].y, acc[t], 0, 0, 0);
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(kv[u].z, qv[u].z, acc[t], 0, 0, 0);
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(kv[u].w, qv[u].w, acc[t], 0, 0, 0);
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) kv[u] = kn[u];
+                for (int u = 0; u < 4; ++u) kv[u] = kn[u];
             }
         }
         // accumulator x of a lane: band row r, key block 16 tile + 4c + x
@@ -268,7 +272,7 @@ __global__ __launch_bounds__(256, 2) void score_select_kernel(
         auto fetch = [&](int step) {
             const int j0 = (step / slices) * kBandKeys, kc = (step % slices) * kBandChunk;
             // a slice lies inside one residue class a of the query block; its partner is class S-1-a
-            const int kb = (S - 1 - (kc >> 7)) * kHeadDim + (kc & (kHeadDim - 1));
+            const int kb = (S - 1 - (kc >> d_log2)) * d + (kc & (d - 1));
             // keys: 128 rows x 16 floats = 512 float4, two per thread; queries: ROWS x 16 floats
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
@@ -366,12 +370,12 @@ int launch_score_select(const Problem& p, int ad_stride, const float* q_bar, con
     dim3 grid(total, p.Hq), block(256);
     if (rows_per_band == 16)
         hipLaunchKernelGGL(score_select_kernel<16>, grid, block, 0, stream, q_bar, k_bar, m_v, budget, counts,
-                           indices, debug_scores, p.seq, bands, p.R, p.Rk, p.NBmax, p.G, ad_stride, beta,
-                           route_scale, n_sink, n_local, kmax);
+                           indices, debug_scores, p.seq, bands, p.R, p.Rk, p.NBmax, p.G, ad_stride,
+                           __builtin_ctz(p.d), beta, route_scale, n_sink, n_local, kmax);
     else
         hipLaunchKernelGGL(score_select_kernel<4>, grid, block, 0, stream, q_bar, k_bar, m_v, budget, counts,
-                           indices, debug_scores, p.seq, bands, p.R, p.Rk, p.NBmax, p.G, ad_stride, beta,
-                           route_scale, n_sink, n_local, kmax);
+                           indices, debug_scores, p.seq, bands, p.R, p.Rk, p.NBmax, p.G, ad_stride,
+                           __builtin_ctz(p.d), beta, route_scale, n_sink, n_local, kmax);
     return check_launch();
 }
 

@@ -122,14 +122,14 @@ def test_anti_diagonal_strides_estimate_and_select(name, ad_stride):
     say("%s S=%d: score err %.3g" % (w.name, ad_stride, err))
 
 
-@pytest.mark.parametrize("ad_stride,fused", [(1, False), (4, True)])
-def test_chunked_prefill_gives_the_rows_of_the_one_piece_call(ad_stride, fused):
+@pytest.mark.parametrize("ad_stride,fused,head_dim", [(1, False, 128), (4, True, 128), (2, False, 64), (1, True, 256)])
+def test_chunked_prefill_gives_the_rows_of_the_one_piece_call(ad_stride, fused, head_dim):
     """A prompt processed in three chunks against its growing KV, with one workspace kept between
     the calls (each call pools only its own blocks): every chunk's scores, lists, outputs and lse
     are bit-identical to the matching rows of the one-piece call, whose parity with the oracle is
     then checked on the assembled output."""
     w = wl.small("chunks_b128", seed=41, num_q_heads=4, num_kv_heads=2, seq_lens=(1536, 700),
-                 block_size=128, k_start=(6, 4), n_sink=1, n_local=2, outliers=(3, 2))
+                 block_size=128, k_start=(6, 4), n_sink=1, n_local=2, outliers=(3, 2), head_dim=head_dim)
     B, cu = w.block_size, list(w.cu_seqlens)
     data = wl.generate(w)
     qkv = pu.host_arrays(data)
@@ -363,8 +363,8 @@ def test_attention_on_given_lists_full_budget_and_random():
 
 
 @pytest.mark.parametrize("sign", [1.0, -1.0])
-@pytest.mark.parametrize("B", [128, 64])
-def test_attention_reference_moves_and_unusable_entries(B, sign):
+@pytest.mark.parametrize("B,d", [(128, 128), (64, 128), (128, 64), (64, 64), (128, 256), (64, 256)])
+def test_attention_reference_moves_and_unusable_entries(B, d, sign):
     """Two things ordinary data does not reach.  (1) Logits far outside the exponent range of a
     fixed reference, growing along the keys and jumping inside blocks, so that the softmax reference
     has to move at every check point of a block (and O is rescaled) - against the oracle's
@@ -374,15 +374,15 @@ def test_attention_reference_moves_and_unusable_entries(B, sign):
     torch.manual_seed(7)
     Hq, Hkv, T = 4, 2, 1536
     cu = [0, 1000, T]
-    q = torch.randn(T, Hq, 128) * 3.0
-    k = torch.randn(T, Hkv, 128)
-    v = torch.randn(T, Hkv, 128)
+    q = torch.randn(T, Hq, d) * 3.0
+    k = torch.randn(T, Hkv, d)
+    v = torch.randn(T, Hkv, d)
     ramp = 1.0 + 6.0 * torch.arange(T).float() / T                     # later keys score higher
     ramp[40::97] *= 3.0                                                # spikes inside blocks
-    k = sign * (k * ramp[:, None, None] + 0.5 * q.view(T, Hkv, 2, 128).mean(2) * ramp[:, None, None])
+    k = sign * (k * ramp[:, None, None] + 0.5 * q.view(T, Hkv, 2, d).mean(2) * ramp[:, None, None])
     q, k, v = (x.to(torch.bfloat16) for x in (q, k, v))
     qkv = tuple(x.float().numpy() for x in (q, k, v))
-    scale = 128 ** -0.5
+    scale = d ** -0.5
     logits = np.einsum("td,sd->ts", qkv[0][:, 0], qkv[1][:, 0]) * scale
     assert np.abs(logits).max() > 200.0                                # e^200 overflows fp32
     R, nbmax = so.total_rows(cu, B)

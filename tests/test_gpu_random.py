@@ -10,7 +10,7 @@ from test_gpu_parity import run_both
 pytestmark = pytest.mark.gpu
 
 
-def random_workload(seed: int) -> wl.Workload:
+def random_workload(seed: int, head_dim: int = 128) -> wl.Workload:
     r = np.random.default_rng(1000 + seed)
     B = int(r.choice([64, 128]))
     hkv = int(r.choice([1, 2, 3]))
@@ -25,7 +25,8 @@ def random_workload(seed: int) -> wl.Workload:
                     block_size=B, k_start=tuple(float(r.integers(0, 9)) + float(r.choice([0.0, 0.4])) for _ in lens),
                     n_sink=int(r.integers(0, 4)), n_local=n_local, outliers=tuple(int(r.integers(0, 3)) for _ in lens),
                     mu=float(r.choice([0.5, 0.7, 1.0])), k_min=int(r.integers(0, 6)),
-                    beta=float(r.choice([0.0, 0.2, 1.0])), route_scale=float(r.choice([1.0, 128 ** -0.5])))
+                    beta=float(r.choice([0.0, 0.2, 1.0])), route_scale=float(r.choice([1.0, 128 ** -0.5])),
+                    head_dim=head_dim)
 
 
 @pytest.mark.parametrize("seed", range(24))
@@ -36,12 +37,26 @@ def test_random_workload_whole_path(seed):
 @pytest.mark.parametrize("seed", range(24, 40))
 def test_random_workload_with_options(seed):
     """The same with a random anti-diagonal stride, the fused stage 1-2 or group-shared lists."""
+    run_with_options(random_workload(seed), seed)
+
+
+@pytest.mark.parametrize("head_dim", [64, 256])
+@pytest.mark.parametrize("seed", range(40, 52))
+def test_random_workload_other_head_sizes(seed, head_dim):
+    """Head sizes 64 and 256: plain on even seeds, with random options on odd ones."""
+    w = random_workload(seed, head_dim)
+    if seed % 2:
+        run_with_options(w, seed)
+    else:
+        run_both(w)
+
+
+def run_with_options(w, seed):
     import torch
     from oracle import stem_oracle as so
     from paper_2603_06274_amd.prefill import StemPrefill
     import parity_util as pu
 
-    w = random_workload(seed)
     r = np.random.default_rng(5000 + seed)
     S = int(r.choice([1, 2, 4, 8]))
     group = [None, "max", "mean"][int(r.integers(0, 3))]

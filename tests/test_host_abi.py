@@ -38,6 +38,11 @@ def test_rows_and_workspace():
         total = sb.stem_workspace_bytes(shape, S)
         assert k_off == 0 and m_off >= 2 * 12 * S * 128 * 4 and q_off >= m_off + 2 * 12 * 4
         assert total >= q_off + 4 * 12 * S * 128 * 4 and q_off % 256 == 0 and m_off % 256 == 0
+        for d in (64, 256):                            # the pooled parts scale with the head size
+            other = make_shape(shape.cu_seqlens, d=d)
+            q_d, k_d, m_d = sb.stem_workspace_layout(other, S)
+            assert k_d == 0 and m_d >= 2 * 12 * S * d * 4 and q_d >= m_d + 2 * 12 * 4
+            assert sb.stem_workspace_bytes(other, S) >= q_d + 4 * 12 * S * d * 4
     n = ctypes.c_size_t()
     L = sb.lib()
     for S, want in ((0, sb.STEM_ERR_INVALID_ARG), (-2, sb.STEM_ERR_INVALID_ARG), (3, sb.STEM_ERR_INVALID_ARG),
@@ -116,7 +121,11 @@ def test_bad_arguments_are_rejected_on_the_host():
     n = ctypes.c_size_t()
     # shape errors
     assert L.stem_workspace_bytes(make_shape([0, 640], Hq=3, Hkv=2).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_workspace_bytes(make_shape([0, 640], d=64).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_UNSUPPORTED
+    assert L.stem_workspace_bytes(make_shape([0, 640], d=96).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_UNSUPPORTED
+    assert L.stem_workspace_bytes(make_shape([0, 640], d=512).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_UNSUPPORTED
+    assert L.stem_workspace_bytes(make_shape([0, 640], d=0).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
+    narrow = sb.Shape(4, 2, 256, 64, [0, 640], (4 * 128, 128), (2 * 128, 128))     # rows narrower than a head
+    assert L.stem_workspace_bytes(narrow.ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_workspace_bytes(make_shape([0, 640], B=32).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_UNSUPPORTED
     assert L.stem_workspace_bytes(make_shape([0, 640, 600]).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_workspace_bytes(make_shape([1, 640]).ref(), 1, ctypes.byref(n)) == sb.STEM_ERR_INVALID_ARG
@@ -154,4 +163,4 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.stem_pool(empty.ref(), 0x1000, 0x1000, 0x1000, 1, 0x1000, 1 << 20, None) == sb.STEM_OK
     assert L.stem_sparse_attn(empty.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 4, 0, 0.1, 0x1000, None, None) == sb.STEM_OK
     with pytest.raises(sb.StemError):
-        sb.stem_rows(make_shape([0, 640], d=64))
+        sb.stem_rows(make_shape([0, 640], d=96))
