@@ -144,9 +144,10 @@ int launch_select(const Problem& p, int heads, const float* scores, const int32_
 // order in which the products walk the depth is free as long as both operands agree: lane
 // (r = lane % 16, c = lane / 16) holds, of its key block or row r, the floats 16u + 4c .. + 3 of
 // every 64-byte group u, so a 16-byte load serves four product steps and the four lanes of a row
-// read 64 contiguous bytes.  Wave w owns the tiles w, w + 4, ...; their accumulators (at most 16
-// tiles x 4 registers) stay in registers across the whole depth, which is walked 64 floats at a
-// time; the next tile's keys are in flight during the products of the current one.
+// read 64 contiguous bytes.  The workgroup has 8 waves; wave w owns the tiles w, w + 8, ...; their
+// accumulators (at most 8 tiles x 4 registers) stay in registers across the whole depth, which is
+// walked 64 floats at a time; the next tile's keys are in flight during the products of the
+// current one.  With 128 registers per lane two such workgroups (16 waves) share a CU.
 // Phase 1, ROWS = 4: fp32 FMAs on 128-key chunks staged through LDS 16 floats of the contraction at
 // a time; wave w accumulates row w against the 128 keys, two adjacent keys per lane.
 // ------------------------------------------------------------------------------------------------
@@ -159,13 +160,14 @@ constexpr int kBandKeys = 128;                         // key blocks per step
 constexpr int kScorePad = 4;                           // floats between rows of sc: 16-byte writes of 16 rows spread over all banks
 
 template <int ROWS>
-__global__ __launch_bounds__(256, 2) void score_select_kernel(
+__global__ __launch_bounds__(ROWS == 16 ? 512 : 256, 2) void score_select_kernel(
     const float* __restrict__ q_bar, const float* __restrict__ k_bar, const float* __restrict__ m_v,
     const int32_t* __restrict__ budget, int32_t* __restrict__ counts, int32_t* __restrict__ indices,
     float* __restrict__ debug_scores, SeqTable seq, BandTable bands, int R, int Rk, int NBmax, int G,
     int S, int d_log2, float beta, float route_scale, int n_sink, int n_local, int kmax) {
     constexpr int NBcap = ROWS == 16 ? 1024 : 4096;    // key blocks per row held in LDS
-    constexpr int RPW = ROWS / 4;                      // rows per wave
+    constexpr int WAVES = ROWS == 16 ? 8 : 4;          // 16-row bands: 8 waves, two rows each in phase 2
+    constexpr int RPW = ROWS / WAVES;                  // rows per wave
     constexpr int ITEMS = NBcap / 64;
     __shared__ __attribute__((aligned(16))) float sc[ROWS][NBcap + kScorePad];
 
@@ -194,7 +196,7 @@ __global__ __launch_bounds__(256, 2) void score_select_kernel(
 
     if constexpr (ROWS == 16) {
         typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
-        constexpr int TPW = NBcap / 16 / 4;            // tiles per wave
+        constexpr int TPW = NBcap / 16 / WAVES;        // tiles per wave
         const int r = lane & 15, c = lane >> 4;
         const int n_tiles = (n_keys + 15) >> 4;
         done = n_tiles * 16;
@@ -224,9 +226,9 @@ __global__ __launch_bounds__(256, 2) void score_select_kernel(
             if (w < n_tiles) load_keys(kv, w);
 #pragma unroll
             for (int t = 0; t < TPW; ++t) {
-                const int tile = 4 * t + w;
+                const int tile = WAVES * t + w;
                 if (tile >= n_tiles) break;            // wave-uniform
-                if (tile + 4 < n_tiles) load_keys(kn, tile + 4);
+                if (tile + WAVES < n_tiles) load_keys(kn, tile + WAVES);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(kv[u].x, qv[u].x, acc[t], 0, 0, 0);
@@ -241,7 +243,7 @@ __global__ __launch_bounds__(256, 2) void score_select_kernel(
         // accumulator x of a lane: band row r, key block 16 tile + 4c + x
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
-            const int tile = 4 * t + w;
+            const int tile = WAVES * t + w;
             if (tile >= n_tiles) break;
             const int j0 = tile * 16 + 4 * c;
             float val[4];
@@ -367,7 +369,7 @@ int launch_score_select(const Problem& p, int ad_stride, const float* q_bar, con
     }
     if (total == 0) return STEM_OK;
     if (p.Hq > 65535) return STEM_ERR_UNSUPPORTED;
-    dim3 grid(total, p.Hq), block(256);
+    dim3 grid(total, p.Hq), block(rows_per_band == 16 ? 512 : 256);
     if (rows_per_band == 16)
         hipLaunchKernelGGL(score_select_kernel<16>, grid, block, 0, stream, q_bar, k_bar, m_v, budget, counts,
                            indices, debug_scores, p.seq, bands, p.R, p.Rk, p.NBmax, p.G, ad_stride,
