@@ -157,6 +157,8 @@ def test_bad_arguments_are_rejected_on_the_host():
     # one sequence of one KV head must stay below 2 GiB for the attention kernel's block addressing
     wide = sb.Shape(4, 2, 128, 64, [0, 4096], (4 * 128, 128), (1 << 19, 128))
     assert L.stem_sparse_attn(wide.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 4, 0, 0.1, 0x1000, None, None) == sb.STEM_ERR_UNSUPPORTED
+    wide64 = sb.Shape(4, 2, 64, 64, [0, 4096], (4 * 64, 64), (1 << 19, 64))       # the same for the other head sizes
+    assert L.stem_sparse_attn(wide64.ref(), 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 4, 0, 0.1, 0x1000, None, None) == sb.STEM_ERR_UNSUPPORTED
     # an empty batch entry list is fine on the host and launches nothing
     empty = make_shape([0, 0])
     assert sb.stem_rows(empty) == (0, 0)
