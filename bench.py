@@ -153,15 +153,15 @@ def main():
     def time_call(fn, n=10):
         fn()
         torch.cuda.synchronize()
-        out = []
-        for _ in range(n):
+        pairs = []
+        for _ in range(n):                             # queued back to back: no host gap inside a pair
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
             fn()
             b.record()
-            b.synchronize()
-            out.append(a.elapsed_time(b))
-        return sum(out) / len(out)
+            pairs.append((a, b))
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in pairs) / n
 
     t_pool = time_call(pf.pool)
     t_scores = time_call(pf.block_scores)
