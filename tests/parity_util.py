@@ -70,7 +70,7 @@ def check_scores(gpu_scores: np.ndarray, scores: np.ndarray):
     safe = np.where(fin, scores, 0.0)
     rms = np.sqrt((safe * safe).sum(axis=2, keepdims=True) / np.maximum(fin.sum(axis=2, keepdims=True), 1))
     tol = SCORE_RTOL * np.maximum(np.abs(safe), rms)
-    err = np.abs(np.where(fin, gpu_scores.astype(np.float64) - scores, 0.0))
+    err = np.abs(np.where(fin, gpu_scores.astype(np.float64), 0.0) - safe)
     worst = float((err / np.maximum(tol, 1e-300)).max())
     assert worst <= 1.0, "score error %.3g x tolerance" % worst
     return float(err.max())
