@@ -99,7 +99,7 @@ def test_magnitude_term_closed_forms():
     v4[8:12, 1] *= 4.0
     _, _, mv4 = so.pool_blocks(q, k, v4, cu, B)
     oam4 = so.oam_scores(qb, kb, mv4, cu, B, beta=beta)
-    delta = np.where(fin, oam4 - oam, 0.0)
+    delta = np.where(fin, oam4, 0.0) - np.where(fin, oam, 0.0)
     want = np.zeros_like(delta)
     want[1, 2:, 2] = beta * math.log(4.0)            # head 1 <-> kv head 1; rows >= 2 see block 2
     assert np.allclose(delta, want, atol=1e-12)
@@ -112,7 +112,7 @@ def test_magnitude_term_closed_forms():
     # norms below one are clamped away; all-zero values give no contribution and no NaN
     assert np.all(mv5[1] < 0)
     s5 = so.oam_scores(qb, kb, mv5, cu, B, beta=1.0)
-    assert np.allclose((s5 - sam)[1][fin[1]], 0.0, atol=1e-12)
+    assert np.allclose(s5[1][fin[1]] - sam[1][fin[1]], 0.0, atol=1e-12)
     _, _, mv0 = so.pool_blocks(q, k, np.zeros_like(v), cu, B)
     s0 = so.oam_scores(qb, kb, mv0, cu, B, beta=1.0)
     assert np.allclose(s0[fin], sam[fin], atol=1e-12) and not np.isnan(s0).any()
