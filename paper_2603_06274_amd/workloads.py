@@ -130,7 +130,14 @@ PACKED_128K = _llama("packed_varlen_128k", 4, (8192, 16384, 32768, 73728), (4, 8
 BENCHMARK_CONFIGS: Dict[str, Workload] = {
     w.name: w for w in [TINY_4K, LLAMA_32K, LLAMA_128K, *SWEEP_64K.values(), PACKED_128K]
 }
-EXTRA_CONFIGS: Dict[str, Workload] = {LLAMA_128K_PAPER_PRESET.name: LLAMA_128K_PAPER_PRESET}
+# The headline layer's shape and schedule with the other two supported head sizes (not benchmark
+# configurations: what the path costs when d is not 128).
+LLAMA_128K_D64 = _llama("llama8b_128k_d64", 2, (131072,), (51,), (64,), target_density=0.08, head_dim=64)
+LLAMA_128K_D256 = _llama("llama8b_128k_d256", 2, (131072,), (51,), (64,), target_density=0.08, head_dim=256)
+
+EXTRA_CONFIGS: Dict[str, Workload] = {
+    w.name: w for w in [LLAMA_128K_PAPER_PRESET, LLAMA_128K_D64, LLAMA_128K_D256]
+}
 
 
 def small(name: str = "small", *, seed: int = 11, num_q_heads: int = 4, num_kv_heads: int = 2,
