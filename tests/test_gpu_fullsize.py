@@ -26,7 +26,7 @@ def say(*a):
 
 def tensors_for(w):
     """The sweep configurations share one set of tensors (same seed and shape)."""
-    key = (w.seed, w.seq_lens, w.num_q_heads, w.num_kv_heads, w.block_size)
+    key = (w.seed, w.seq_lens, w.num_q_heads, w.num_kv_heads, w.block_size, w.head_dim)
     if key not in _cache:
         _cache.clear()
         data = wl.generate(w)
@@ -90,6 +90,12 @@ def test_llama_32k():
 
 def test_llama_128k_headline():
     full_size_case(wl.LLAMA_128K, 16, heads=[0, 9, 22, 31])
+
+
+@pytest.mark.parametrize("d", [64, 256])
+def test_llama_128k_other_head_sizes(d):
+    """The headline layer's shape and schedule at the two other head sizes."""
+    full_size_case(wl.EXTRA_CONFIGS["llama8b_128k_d%d" % d], 8, heads=[0, 22])
 
 
 @pytest.mark.parametrize("point", ["d100", "d50", "d20", "d10", "d5"])
