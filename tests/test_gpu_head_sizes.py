@@ -33,3 +33,25 @@ def cases(d):
 @pytest.mark.parametrize("d", [64, 256])
 def test_head_size_whole_path(d, name):
     run_both(cases(d)[name])
+
+
+@pytest.mark.parametrize("d,ad_stride", [(64, 1), (256, 2)])
+def test_head_size_fused_above_1024_blocks(d, ad_stride):
+    """The fused stage 1-2 with more than 1024 key blocks per row (its 4-row bands) at the other head
+    sizes: dumped scores and lists against the oracle."""
+    import torch
+    import parity_util as pu
+    w = wl.small("many_blocks_d%d" % d, seed=65, num_q_heads=2, num_kv_heads=1, seq_lens=(1100 * 64 + 5,),
+                 block_size=64, k_start=(30,), n_sink=2, n_local=2, outliers=(8,), head_dim=d)
+    data = wl.generate(w)
+    qkv = pu.host_arrays(data)
+    pf = pu.device_prefill(w, data, ad_stride=ad_stride)
+    assert pf.nbmax > 1024
+    dump = torch.full_like(pf.scores, float("nan"))
+    pf.estimate_select(dump)
+    torch.cuda.synchronize()
+    scores = pu.oracle_estimate(w, qkv, ad_stride)[3]
+    pu.check_scores(dump.cpu().numpy(), scores)
+    _, counts, indices = pu.oracle_select(w, scores)
+    same = pu.check_lists(w, pf.counts.cpu().numpy(), pf.indices.cpu().numpy(), counts, indices, scores, print)
+    assert same.mean() > 0.99
