@@ -148,15 +148,13 @@ int launch_select(const Problem& p, int heads, const float* scores, const int32_
 // accumulators (at most 8 tiles x 4 registers) stay in registers across the whole depth, which is
 // walked 64 floats at a time; the next tile's keys are in flight during the products of the
 // current one.  With 128 registers per lane two such workgroups (16 waves) share a CU.
-// Phase 1, ROWS = 4: fp32 FMAs on 128-key chunks staged through LDS 16 floats of the contraction at
-// a time; wave w accumulates row w against the 128 keys, two adjacent keys per lane.
+// Phase 1, ROWS = 4: v_mfma_f32_4x4x1_16B_f32 on 256-key chunks staged through LDS 8 floats of the
+// contraction at a time; every wave takes 64 keys against the band's four rows.
 // ------------------------------------------------------------------------------------------------
 struct BandTable {
     int32_t band_start[STEM_MAX_BATCH + 1];            // prefix sums of ceil(rows of the call / ROWS)
 };
 
-constexpr int kBandChunk = 16;                         // floats of the contraction staged per step
-constexpr int kBandKeys = 128;                         // key blocks per step
 constexpr int kScorePad = 4;                           // floats between rows of sc: 16-byte writes of 16 rows spread over all banks
 
 template <int ROWS>
@@ -166,8 +164,8 @@ __global__ __launch_bounds__(ROWS == 16 ? 512 : 256, 2) void score_select_kernel
     float* __restrict__ debug_scores, SeqTable seq, BandTable bands, int R, int Rk, int NBmax, int G,
     int S, int d_log2, float beta, float route_scale, int n_sink, int n_local, int kmax) {
     constexpr int NBcap = ROWS == 16 ? 1024 : 4096;    // key blocks per row held in LDS
-    constexpr int WAVES = ROWS == 16 ? 8 : 4;          // 16-row bands: 8 waves, two rows each in phase 2
-    constexpr int RPW = ROWS / WAVES;                  // rows per wave
+    constexpr int WAVES = ROWS == 16 ? 8 : 4;
+    constexpr int RPW = ROWS / WAVES;                  // rows per wave in phase 2
     constexpr int ITEMS = NBcap / 64;
     __shared__ __attribute__((aligned(16))) float sc[ROWS][NBcap + kScorePad];
 
@@ -263,74 +261,73 @@ __global__ __launch_bounds__(ROWS == 16 ? 512 : 256, 2) void score_select_kernel
             }
         }
     } else {
-        __shared__ __attribute__((aligned(16))) float ks[kBandChunk][kBandKeys + 2];   // [contraction][key]
-        __shared__ __attribute__((aligned(16))) float qs[kBandChunk][ROWS];            // [contraction][row]
-        // The (key chunk, contraction slice) steps run as one sequence with the next step's global
-        // loads in flight while the current one is computed.
-        const int slices = depth / kBandChunk;         // per key chunk
-        const int steps = (n_keys + kBandKeys - 1) / kBandKeys * slices;
-        done = (n_keys + kBandKeys - 1) / kBandKeys * kBandKeys;
-        float4 bv[2], av;
+        // 4-row bands: v_mfma_f32_4x4x1_16B_f32, sixteen independent 4 x 4 outer products per
+        // instruction: block l / 4 of the wave pairs the band's row l % 4 (A operand) with key
+        // block 4 (l / 4) + l % 4 = l of the wave's 64 (B operand), and lane l ends up with the four
+        // rows' scores of its key block.  Keys are staged through LDS 256 at a time (64 per wave),
+        // 8 floats of the contraction per step, row-major with 48-byte rows, so a lane's 16-byte
+        // reads of its own key row are conflict-free; the next step's global loads are in flight
+        // during the products.  The staging is kept this small so that, next to the 64 KiB of
+        // scores, two workgroups fit a CU: the selection phase of one then runs beside the score
+        // phase of the other.
+        typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+        constexpr int kKeys = 64 * WAVES, kSlice = 8, kPad = kSlice + 4;
+        __shared__ __attribute__((aligned(16))) float ks[kKeys][kPad];   // [key][contraction]
+        __shared__ __attribute__((aligned(16))) float qs[ROWS][kPad];    // [row][contraction]
+        const int slices = depth / kSlice;             // per key chunk
+        const int chunks = (n_keys + kKeys - 1) / kKeys;
+        const int steps = chunks * slices;
+        done = chunks * kKeys;
+        constexpr int kPerThread = kKeys * (kSlice / 4) / (64 * WAVES);   // float4 per thread and step
+        float4 bv[kPerThread], av;
         auto fetch = [&](int step) {
-            const int j0 = (step / slices) * kBandKeys, kc = (step % slices) * kBandChunk;
+            const int j0 = (step / slices) * kKeys, kc = (step % slices) * kSlice;
             // a slice lies inside one residue class a of the query block; its partner is class S-1-a
             const int kb = (S - 1 - (kc >> d_log2)) * d + (kc & (d - 1));
-            // keys: 128 rows x 16 floats = 512 float4, two per thread; queries: ROWS x 16 floats
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int idx = tid + 256 * u;
-                const int row = idx >> 2, c4 = (idx & 3) * 4;
+            for (int u = 0; u < kPerThread; ++u) {
+                const int idx = tid + 64 * WAVES * u;
+                const int row = idx / (kSlice / 4), c4 = (idx % (kSlice / 4)) * 4;
                 bv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (j0 + row < n_keys) bv[u] = *reinterpret_cast<const float4*>(b_src + (int64_t)(j0 + row) * depth + kb + c4);
             }
             av = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (tid < ROWS * 4 && (tid >> 2) < band_rows)
-                av = *reinterpret_cast<const float4*>(a_src + (int64_t)(tid >> 2) * depth + kc + (tid & 3) * 4);
+            if (tid < ROWS * (kSlice / 4) && tid / (kSlice / 4) < band_rows)
+                av = *reinterpret_cast<const float4*>(a_src + (int64_t)(tid / (kSlice / 4)) * depth + kc + (tid % (kSlice / 4)) * 4);
         };
-        float acc[RPW][2];
-#pragma unroll
-        for (int x = 0; x < RPW; ++x) acc[x][0] = acc[x][1] = 0.f;
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
         if (steps > 0) fetch(0);
         for (int step = 0; step < steps; ++step) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int idx = tid + 256 * u;
-                const int row = idx >> 2, c4 = (idx & 3) * 4;
-                ks[c4 + 0][row] = bv[u].x; ks[c4 + 1][row] = bv[u].y; ks[c4 + 2][row] = bv[u].z; ks[c4 + 3][row] = bv[u].w;
+            for (int u = 0; u < kPerThread; ++u) {
+                const int idx = tid + 64 * WAVES * u;
+                *reinterpret_cast<float4*>(&ks[idx / (kSlice / 4)][(idx % (kSlice / 4)) * 4]) = bv[u];
             }
-            if (tid < ROWS * 4) {
-                const int row = tid >> 2, c4 = (tid & 3) * 4;
-                qs[c4 + 0][row] = av.x; qs[c4 + 1][row] = av.y; qs[c4 + 2][row] = av.z; qs[c4 + 3][row] = av.w;
-            }
+            if (tid < ROWS * (kSlice / 4))
+                *reinterpret_cast<float4*>(&qs[tid / (kSlice / 4)][(tid % (kSlice / 4)) * 4]) = av;
             __syncthreads();
             if (step + 1 < steps) fetch(step + 1);
 #pragma unroll
-            for (int kk = 0; kk < kBandChunk; ++kk) {
-                const float2 kv = *reinterpret_cast<const float2*>(&ks[kk][2 * lane]);
-#pragma unroll
-                for (int x = 0; x < RPW; ++x) {
-                    const float qv = qs[kk][w * RPW + x];
-                    acc[x][0] = fmaf(qv, kv.x, acc[x][0]);
-                    acc[x][1] = fmaf(qv, kv.y, acc[x][1]);
-                }
+            for (int u = 0; u < kSlice / 4; ++u) {
+                const float4 kf = *reinterpret_cast<const float4*>(&ks[w * 64 + lane][4 * u]);
+                const float4 qf = *reinterpret_cast<const float4*>(&qs[lane & 3][4 * u]);
+                acc = __builtin_amdgcn_mfma_f32_4x4x1f32(qf.x, kf.x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_4x4x1f32(qf.y, kf.y, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_4x4x1f32(qf.z, kf.z, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_4x4x1f32(qf.w, kf.w, acc, 0, 0, 0);
             }
             __syncthreads();
             if (step % slices == slices - 1) {         // the chunk's contraction is complete
-                const int j0 = (step / slices) * kBandKeys;
+                const int j = (step / slices) * kKeys + w * 64 + lane;
+                const float mag = (j < n_keys) ? beta * fmaxf(0.f, mag_src[j]) : 0.f;
 #pragma unroll
-                for (int y = 0; y < 2; ++y) {
-                    const int j = j0 + 2 * lane + y;
-                    const float mag = (j < n_keys) ? beta * fmaxf(0.f, mag_src[j]) : 0.f;
-#pragma unroll
-                    for (int x = 0; x < RPW; ++x) {
-                        const int row = w * RPW + x;
-                        const float val = (j <= first + ic0 + row) ? fmaf(route_scale / (float)S, acc[x][y], mag) : neg_inf;
-                        acc[x][y] = 0.f;
-                        if (row >= band_rows || j >= NBcap) continue;
-                        sc[row][j] = val;
-                        if (dbg != nullptr && j < NBmax) dbg[(int64_t)row * NBmax + j] = val;
-                    }
+                for (int row = 0; row < ROWS; ++row) {
+                    const float val = (j <= first + ic0 + row) ? fmaf(route_scale / (float)S, acc[row], mag) : neg_inf;
+                    if (row >= band_rows || j >= NBcap) continue;
+                    sc[row][j] = val;
+                    if (dbg != nullptr && j < NBmax) dbg[(int64_t)row * NBmax + j] = val;
                 }
+                acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
             }
         }
     }
