@@ -91,6 +91,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama8b_128k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ad-stride", type=int, default=1, help="anti-diagonal stride of the estimate (1, 2, 4, 8, 16)")
+    ap.add_argument("--fused", action="store_true", help="stages 1-2 through stem_estimate_select (no score tensor)")
+    ap.add_argument("--group-share", choices=["max", "mean"], default=None,
+                    help="one list per (KV head, row) from the group-reduced metric")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size dispatch the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -108,8 +112,13 @@ def main():
     w = {**workloads.BENCHMARK_CONFIGS, **workloads.EXTRA_CONFIGS}[args.workload]
     data = workloads.generate(w)
     dev = torch.device("cuda:0")
+    if args.fused and args.group_share:
+        sys.exit("bench.py: --fused gives per-head lists only")
+    options = {"ad_stride": args.ad_stride, "fused": args.fused, "group_share": args.group_share}
+    default_options = args.ad_stride == 1 and not args.fused and not args.group_share
     pf = StemPrefill(*(data[x].to(dev) for x in "qkv"), w.cu_seqlens, w.block_size, w.k_start_blocks, w.mu,
-                     w.k_min, w.n_sink, w.n_local, w.beta, w.route_scale, w.softmax_scale)
+                     w.k_min, w.n_sink, w.n_local, w.beta, w.route_scale, w.softmax_scale,
+                     ad_stride=args.ad_stride, group_share=args.group_share)
 
     d, B, Hq, Hkv, T, R = w.head_dim, w.block_size, w.num_q_heads, w.num_kv_heads, w.total_tokens, w.total_rows
     dense_flops = 4.0 * d * B * B * w.admissible_blocks * Hq
@@ -122,7 +131,7 @@ def main():
         del src, dst
 
     for _ in range(args.warmup):
-        pf.run()
+        pf.run(fused=args.fused)
     torch.cuda.synchronize()
 
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
@@ -130,9 +139,13 @@ def main():
     t0 = time.perf_counter()
     for s in range(args.steps):
         ev[s][0].record()
-        pf.estimate()
-        ev[s][1].record()
-        pf.select()
+        if args.fused:                                 # both stages in one call: booked under "estimate"
+            pf.estimate_select()
+            ev[s][1].record()
+        else:
+            pf.estimate()
+            ev[s][1].record()
+            pf.select()
         ev[s][2].record()
         pf.attend()
         ev[s][3].record()
@@ -145,6 +158,8 @@ def main():
     t_attn_avg = sum(attn_ms) / len(attn_ms)
 
     listed = int(pf.counts.sum().item())
+    if args.group_share:                               # a list serves the G heads of its KV head
+        listed *= Hq // Hkv
     density = listed / (w.admissible_blocks * Hq)
     attn_flops = 4.0 * d * B * B * listed
     attn_tflops = attn_flops / (t_attn_avg * 1e-3) / 1e12
@@ -165,7 +180,7 @@ def main():
 
     t_pool = time_call(pf.pool)
     t_scores = time_call(pf.block_scores)
-    pool_bytes = 2.0 * d * T * (Hq + 2 * Hkv) + 4.0 * d * R * (Hq + Hkv) + 4.0 * R * Hkv
+    pool_bytes = 2.0 * d * T * (Hq + 2 * Hkv) + 4.0 * d * R * (Hq + Hkv) * args.ad_stride + 4.0 * R * Hkv
     pool_gbs = pool_bytes / (t_pool * 1e-3) / 1e9
 
     value = dense_flops / (ms_per_step * 1e-3) / 1e12
@@ -182,18 +197,18 @@ def main():
         "config": {"workload": w.name, "tokens": T, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d, "block": B,
                    "k_start_blocks": list(w.k_start_blocks), "mu": w.mu, "beta": w.beta,
                    "n_sink": w.n_sink, "n_local": w.n_local, "density": round(density, 5),
-                   "listed_blocks": listed},
+                   "listed_blocks": listed, **({} if default_options else options)},
         "stages_ms": {"estimate": round(t_est, 4), "select": round(t_sel, 4), "attention": round(t_attn_avg, 4),
                       "pool_kernel": round(t_pool, 4), "scores_kernel": round(t_scores, 4)},
         "attention_dense_equiv_tflops": round(dense_flops / (t_attn_avg * 1e-3) / 1e12, 2),
         "roofline": {"kernel": "sparse_attn_kernel" if d == 128 else "sparse_attn_generic_kernel", "bound": "mfma", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(w.name)},
+                     "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(w.name) if default_options else None},
         "estimate_roofline": {"kernel": "pool_kernel", "bound": "hbm", "achieved": round(pool_gbs, 1),
                               "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(pool_gbs / PEAK_HBM_GBS, 4),
                               "algorithmic_bytes": pool_bytes},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and default_options:   # the oracle leg times the default path only
         result["cpu_baseline"] = cpu_baseline(w, data, dense_flops)
     print(json.dumps(result), flush=True)
 
