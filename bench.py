@@ -201,7 +201,7 @@ def main():
         "stages_ms": {"estimate": round(t_est, 4), "select": round(t_sel, 4), "attention": round(t_attn_avg, 4),
                       "pool_kernel": round(t_pool, 4), "scores_kernel": round(t_scores, 4)},
         "attention_dense_equiv_tflops": round(dense_flops / (t_attn_avg * 1e-3) / 1e12, 2),
-        "roofline": {"kernel": "sparse_attn_kernel" if d == 128 else "sparse_attn_generic_kernel", "bound": "mfma", "achieved": round(attn_tflops, 2),
+        "roofline": {"kernel": "sparse_attn_kernel", "bound": "mfma", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(w.name) if default_options else None},
         "estimate_roofline": {"kernel": "pool_kernel", "bound": "hbm", "achieved": round(pool_gbs, 1),

@@ -36,9 +36,8 @@
  *     sequence for the schedule, the causal limit and the windows, so the chunks of a prompt give
  *     the rows of the one-piece call.  chunk_start must be a multiple of B, chunk_end a multiple
  *     of B or the sequence's length; an empty chunk (start == end) contributes nothing.
- *   - Supported: head_dim 64, 128 or 256 (the attention kernel tuned for this GPU is the one for
- *     128; the other two sizes run a plainer kernel of the same arithmetic); block_size 64 or 128;
- *     1 <= batch <= STEM_MAX_BATCH; Hq a multiple of Hkv; at most STEM_MAX_BLOCKS blocks per sequence.
+ *   - Supported: head_dim 64, 128 or 256; block_size 64 or 128; 1 <= batch <= STEM_MAX_BATCH; Hq a
+ *     multiple of Hkv; at most STEM_MAX_BLOCKS blocks per sequence.
  */
 #ifndef STEM_H
 #define STEM_H

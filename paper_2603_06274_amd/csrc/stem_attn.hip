@@ -16,7 +16,8 @@
 // registers), one buffer each, refilled in split phases behind two barriers per block: the V block
 // is requested during the first half of S^T and must have landed when S^T ends; the next K block
 // is requested during O^T and must have landed when the next iteration starts.  Two workgroups
-// share a CU, so one workgroup's matrix work fills the other's waits.
+// share a CU, so one workgroup's matrix work fills the other's waits (at head size 256 the two
+// 64 KiB buffers and about 490 registers leave room for one).
 //
 // Inside a wave the instruction stream is kept dense around the matrix instructions: LDS operands
 // are read six matrix instructions ahead into a ring of registers, the softmax of a block is
@@ -24,15 +25,18 @@
 // quarters of O^T), and the softmax runs without a running maximum: a per-query reference is set
 // on the first block and moved only when a window of probabilities overflows (slow path).
 //
-// LDS layouts (256-byte rows): K has its 16-byte chunks XORed with (row & 15), so the 32 rows a
-// b128 operand read touches spread over all banks; V has its 64-byte groups XORed with (row & 3),
-// which does the same for the 4-row x 64-byte footprint of a transposing read.  The swizzle is
-// applied on the global side (each lane fetches the chunk that belongs at its LDS position).
+// The kernel is a template over the block size B (64, 128) and the head size D (64, 128, 256); the
+// headline shape (128, 128) has its own hand-placed softmax schedule, the others a generic one.
+//
+// LDS layouts (rows of 2 D bytes, unpadded: the direct loads write 1 KiB contiguously): K has its
+// 16-byte chunks XORed with (row & 15), so the 16 rows a quarter-wave reads one chunk of spread
+// over all banks; V has its 64-byte groups XORed with (row & 3), which does the same for the
+// 4-row x 32-byte footprint of a transposing read.  At D = 64 two 128-byte rows share the 64
+// banks, so the terms are ((row >> 1) & 7) and ((row >> 1) & 1) there.  The swizzle is applied on
+// the global side (each lane fetches the chunk that belongs at its LDS position).
 #include "stem_common.h"
 
 namespace stem {
-
-constexpr int kHeadDim = 128;                          // the head size this kernel is built for
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
@@ -80,11 +84,9 @@ __device__ __forceinline__ void wait_lgkmcnt(int n) {   // n is a constant after
 // matrix instructions that consume the current group.
 #define STEM_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-constexpr int kRowBytes = kHeadDim * 2;               // one K or V row in LDS
-
-// One 1 KiB slice (4 rows) of a B x 128 bf16 block, global -> LDS.  A block is 8 slices per wave:
-// wave w issues slices u*NW + w, u = 0..7, so that the row's swizzle term does not depend on u (for
-// B = 64 it depends on the parity of u only).  Requests are issued one at a time between matrix
+// One 1 KiB slice (1024 / 2D rows) of a B x D bf16 block, global -> LDS.  A block is D / 16 slices
+// per wave: wave w issues slices u*NW + w, so that the row's swizzle term depends on u with a short
+// period only (1, 2 or 4).  Requests are issued one at a time between matrix
 // instructions, never as a burst: the texture-address unit takes a wave's 1 KiB request at
 // 64 B/clk, and a wave that finds its queue full cannot issue anything else.
 //
@@ -93,73 +95,104 @@ constexpr int kRowBytes = kHeadDim * 2;               // one K or V row in LDS
 // past the end of a partial last block (and past the end of the tensor) are never read and arrive
 // in LDS as zeros (their keys are masked by causality, their values get weight 0).  A block is a
 // byte offset added to the per-lane offset (one vector add per block), a slice one more add.
+template <int NV>
 struct BlockRequest {
     __amdgpu_buffer_rsrc_t rsrc;
-    uint32_t lane_off[2];           // block offset + per-lane byte offset, for even / odd u
+    uint32_t lane_off[NV];          // block offset + per-lane byte offset, for u % NV (the swizzle term of a
+                                    // slice's rows repeats with period NV = 1, 2 or 4 in u)
 
     __device__ __forceinline__ void issue(int u, unsigned char* __restrict__ slice0, uint32_t slice_step,
                                           int slice_lds_step) const {
         // slice0 = LDS address of this wave's slice for u = 0; slice u lies u*NW KiB further on
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_t*)(slice0 + u * slice_lds_step), 16,
-                                                 lane_off[u & 1] + u * slice_step, 0, 0, 0);
+                                                 lane_off[u % NV] + u * slice_step, 0, 0, 0);
     }
 };
 
 // raw buffer (stride 0): num_records in bytes, loads beyond it return zero; 0x00020000 is the
 // gfx9-family descriptor word for untyped 32-bit data
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t sequence_resource(const uint16_t* first_row, int rows,
-                                                                    int64_t row_bytes) {
-    const int64_t bytes = rows > 0 ? (int64_t)(rows - 1) * row_bytes + kHeadDim * 2 : 0;   // < 2^31 (host check)
+                                                                    int64_t row_bytes, int head_bytes) {
+    const int64_t bytes = rows > 0 ? (int64_t)(rows - 1) * row_bytes + head_bytes : 0;   // < 2^31 (host check)
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(first_row), 0, (int)bytes, 0x00020000);
 }
 
 // When the softmax pairs of a block are issued and where its reference may be checked, for KT
-// 32-key tiles per block.  Slot s = 0 .. 2*NS-1 counts the wave's matrix instructions of one block
-// (S^T first, then O^T).  Pair q = 8*t + x/2 may be issued once tile t of S^T is complete (slot
-// 8t+7) and must be done before O^T reaches its 16 keys (slot NS + 8t + 4*((q%8)/4)).  At a check
+// 32-key tiles per block and KS = D / 16 matrix instructions per S^T tile.  Slot s = 0 .. 2*NS-1
+// counts the wave's matrix instructions of one block (S^T first, then O^T).  Pair q = 8*t + x/2 may
+// be issued once tile t of S^T is complete (slot KS*t + KS - 1) and must be done before O^T reaches
+// its 16 keys (slot NS + DT*(2t + (q%8)/4), DT = KS / 2 instructions per 16-key step).  At a check
 // slot every pair issued so far must be either consumed by O^T already or part of the window being
 // checked (the pairs issued since the previous check), so that moving the reference there leaves
 // no stale probability behind.  valid() states exactly that and is asserted at compile time.
-template <int KT>
+template <int KT, int KS>
 struct SoftmaxSchedule {
-    static constexpr int NS = KT * 8;                  // matrix instructions per product and block
+    static constexpr int NS = KT * KS;                 // matrix instructions per product and block
+    static constexpr int DT = KS / 2;                  // matrix instructions per 16-key step of O^T
     static constexpr int NP = KT * 8;                  // accumulator pairs per block and lane
-    static constexpr int kChecks = KT == 4 ? 3 : 2;
-    static constexpr int check_slot(int c) { return c == 0 ? NS : c == 1 ? (KT == 4 ? 48 : 24) : 56; }
-    // pairs issued once slot `slot` is issued: four tiles - tiles 0..2 at two pairs per three slots
-    // from slot 8 on, tile 3 one per slot from slot 48 on; two tiles - one per slot from slot 8 on
+    static constexpr bool kTuned = KT == 4 && KS == 8; // the headline shape has a schedule of its own
+    static constexpr int kChecks = kTuned ? 3 : 2;
+    static constexpr int kMaxPerSlot = KS < 8 ? 2 : 1;
+    // Generic: a check when O^T starts (tiles 0 .. KT-2 issued, nothing consumed) and one when O^T
+    // reaches the last tile (its pairs issued, all others consumed).
+    static constexpr int check_slot(int c) {
+        if (kTuned) return c == 0 ? NS : c == 1 ? 48 : 56;
+        return c == 0 ? NS : NS + KS * (KT - 1);
+    }
+    // slot after whose matrix instruction pair q is issued, generic rule: the eight pairs of tile t
+    // spread over the KS slots that follow the tile's completion
+    static constexpr int issue_slot(int q) { return (q / 8 + 1) * KS + ((q % 8) * KS) / 8; }
+    // pairs issued once slot `slot` is issued.  Headline shape: tiles 0..2 at two pairs per three
+    // slots from slot 8 on, tile 3 one per slot from slot 48 on.
     static constexpr int pairs_by(int slot) {
-        if (slot < 8) return 0;
-        if (KT != 4) return slot - 7 > NP ? NP : slot - 7;
-        if (slot < 48) return ((slot - 7) * 2) / 3 > 24 ? 24 : ((slot - 7) * 2) / 3;
-        return 24 + (slot - 47) > NP ? NP : 24 + (slot - 47);
+        if (kTuned) {
+            if (slot < 8) return 0;
+            if (slot < 48) return ((slot - 7) * 2) / 3 > 24 ? 24 : ((slot - 7) * 2) / 3;
+            return 24 + (slot - 47) > NP ? NP : 24 + (slot - 47);
+        }
+        int n = 0;
+        for (int q = 0; q < NP; ++q) n += issue_slot(q) <= slot ? 1 : 0;
+        return n;
     }
     static constexpr bool valid() {
         for (int s = 0; s < 2 * NS; ++s) {
             const int before = s == 0 ? 0 : pairs_by(s - 1), now = pairs_by(s);
-            if (now < before || now > before + 1) return false;            // at most one pair per slot
-            if (now > before) {
-                const int q = before, t = q / 8;
-                if (s <= 8 * t + 7) return false;                            // its S^T tile is complete
-                if (s >= NS + 8 * t + 4 * ((q % 8) / 4)) return false;       // O^T has not reached it
+            if (now < before || now > before + kMaxPerSlot) return false;
+            for (int q = before; q < now; ++q) {
+                const int t = q / 8;
+                if (s <= KS * t + KS - 1) return false;                      // its S^T tile is complete
+                if (s >= NS + DT * (2 * t + (q % 8) / 4)) return false;      // O^T has not reached it
             }
         }
         int lo = 0;
         for (int c = 0; c < kChecks; ++c) {
             const int slot = check_slot(c);
-            if (slot < NS || slot % 4) return false;
-            if (lo > slot - NS) return false;          // pairs below the window are consumed (4 per 4 slots)
+            if (slot < NS || slot % DT) return false;
+            if (lo > 4 * ((slot - NS) / DT)) return false;   // pairs below the window are consumed (4 per step)
             lo = pairs_by(slot - 1);
         }
         return lo == NP && pairs_by(2 * NS - 1) == NP;
     }
+    // pairs_by as a table (entry slot + 1; entry 0 stands for "before slot 0"), so that the unrolled
+    // kernel indexes registers with literal constants
+    struct Table {
+        int v[2 * NS + 1];
+    };
+    static constexpr Table make_table() {
+        Table t{};
+        for (int s = 0; s < 2 * NS; ++s) t.v[s + 1] = pairs_by(s);
+        return t;
+    }
+    static constexpr Table kTable = make_table();
 };
-static_assert(SoftmaxSchedule<4>::valid() && SoftmaxSchedule<2>::valid(), "softmax schedule");
+static_assert(SoftmaxSchedule<4, 8>::valid() && SoftmaxSchedule<2, 8>::valid(), "softmax schedule, d = 128");
+static_assert(SoftmaxSchedule<4, 16>::valid() && SoftmaxSchedule<2, 16>::valid(), "softmax schedule, d = 256");
+static_assert(SoftmaxSchedule<4, 4>::valid() && SoftmaxSchedule<2, 4>::valid(), "softmax schedule, d = 64");
 
 // The body takes the two LDS buffers as __restrict__ parameters: once inlined, every access carries
 // alias-scope information, which lets the compiler's wait-count insertion tell a read of one buffer
 // from an in-flight global->LDS load into the other (otherwise it waits for all of them).
-template <int B>
+template <int B, int D>
 __device__ __forceinline__ void sparse_attn_body(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ counts, const int32_t* __restrict__ indices,
@@ -168,6 +201,16 @@ __device__ __forceinline__ void sparse_attn_body(
     float scale, int items_per_xcd, int xcds_per_kv_head, unsigned char* __restrict__ k_lds,
     unsigned char* __restrict__ v_lds) {
     constexpr int KT = B / 32;                         // 32-key tiles per block
+    constexpr int KS = D / 16;                         // 16-wide steps of S^T along d; also requests per wave, tensor and block
+    constexpr int DT = D / 32;                         // 32-row tiles of O^T along d
+    constexpr int NW = B / 32;                         // waves
+    constexpr int kRowBytes = D * 2;                   // one K or V row in LDS
+    constexpr int kSliceRows = 1024 / kRowBytes;       // rows one wave-wide 1 KiB request covers
+    // LDS swizzles, as XORs on the 16-byte chunk index of a row: K spreads the 16 rows a quarter-wave
+    // reads one chunk of over all banks, V the 4 rows x 32 bytes of a transposing read (at d = 64 two
+    // 128-byte rows share the 64 banks, so the row's bit 0 does the spreading by itself)
+    auto k_swz = [](int row) { return D == 64 ? (row >> 1) & 7 : row & 15; };
+    auto v_swz = [](int row) { return (D == 64 ? (row >> 1) & 1 : row & 3) << 2; };
 
     // ---- which (head, row): consecutive workgroup ids go to different XCDs (each with its own
     // L2), so an XCD should see few KV heads, and all XCDs equal work.  With xcds_per_kv_head = m > 0
@@ -211,28 +254,35 @@ __device__ __forceinline__ void sparse_attn_body(
     const uint16_t* k_head = k + (int64_t)g * kv_sh;
     const uint16_t* v_head = v + (int64_t)g * kv_sh;
 
-    // per-lane byte offsets of the block requests (BlockRequest): lane l of wave w fetches the
-    // 16-byte chunk that belongs at chunk l%16 of row 4w + l/16 of its slice, i.e. the swizzle is
-    // applied to the global column
+    // per-lane byte offsets of the block requests (BlockRequest): slice u of wave w is the 1 KiB at
+    // LDS offset (u NW + w) KiB; lane l writes chunk pc of row (u NW + w) kSliceRows + slice_row there
+    // and fetches the chunk that belongs at that position, i.e. the swizzle is applied to the global
+    // column.  Only the low bits of the row enter the swizzle, so it repeats in u with a short period.
     const int64_t row_bytes = kv_st * 2;
-    const int lrow = w * 4 + (lane >> 4), pc = lane & 15;
+    const int slice_row = (lane * 16) / kRowBytes, pc = ((lane * 16) % kRowBytes) >> 4;
+    const int lrow = w * kSliceRows + slice_row;       // row of slice u = 0
     const uint32_t lane_row_off = (uint32_t)(lrow * row_bytes);
-    const uint32_t k_off_even = lane_row_off + ((pc ^ (lrow & 15)) << 4);
-    const uint32_t k_off_odd = (B == 128) ? k_off_even : lane_row_off + ((pc ^ ((lrow + 8) & 15)) << 4);
-    const uint32_t v_off = lane_row_off + ((pc ^ ((lrow & 3) << 2)) << 4);
-    const auto k_rsrc = sequence_resource(k_head + (int64_t)seq_lo * kv_st, seq_hi - seq_lo, row_bytes);
-    const auto v_rsrc = sequence_resource(v_head + (int64_t)seq_lo * kv_st, seq_hi - seq_lo, row_bytes);
+    constexpr int kKVariants = D == 256 ? (B == 128 ? 2 : 4) : (D == 128 && B == 64) ? 2 : 1;
+    uint32_t k_off[kKVariants];
+#pragma unroll
+    for (int x = 0; x < kKVariants; ++x) k_off[x] = lane_row_off + ((pc ^ k_swz(lrow + x * NW * kSliceRows)) << 4);
+    const uint32_t v_off = lane_row_off + ((pc ^ v_swz(lrow)) << 4);   // NW kSliceRows is a multiple of 4
+    const auto k_rsrc = sequence_resource(k_head + (int64_t)seq_lo * kv_st, seq_hi - seq_lo, row_bytes, kRowBytes);
+    const auto v_rsrc = sequence_resource(v_head + (int64_t)seq_lo * kv_st, seq_hi - seq_lo, row_bytes, kRowBytes);
     const uint32_t block_bytes = (uint32_t)(B * row_bytes);
-    const uint32_t slice_step = (uint32_t)((B / 32) * 4 * row_bytes);   // rows of slices u and u+1 of one wave
-    constexpr int slice_lds_step = (B / 32) * 1024;
+    const uint32_t slice_step = (uint32_t)(NW * kSliceRows * row_bytes);   // rows of slices u and u+1 of one wave
+    constexpr int slice_lds_step = NW * 1024;
     // !real: an offset beyond any sequence, so that nothing is fetched (zeros land in LDS)
     auto k_request = [&](int j, bool real) {
         const uint32_t off = real ? j * block_bytes : 0x80000000u;
-        return BlockRequest{k_rsrc, {k_off_even + off, k_off_odd + off}};
+        BlockRequest<kKVariants> rq{k_rsrc, {}};
+#pragma unroll
+        for (int x = 0; x < kKVariants; ++x) rq.lane_off[x] = k_off[x] + off;
+        return rq;
     };
     auto v_request = [&](int j) {
         const uint32_t off = j * block_bytes;
-        return BlockRequest{v_rsrc, {v_off + off, v_off + off}};
+        return BlockRequest<1>{v_rsrc, {v_off + off}};
     };
     unsigned char* k_slice0 = k_lds + w * 1024;        // this wave's first request slice
     unsigned char* v_slice0 = v_lds + w * 1024;
@@ -250,24 +300,24 @@ __device__ __forceinline__ void sparse_attn_body(
     if (cnt > 0) {
         const auto rq = k_request(clamped(j_cur), true);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) rq.issue(u, k_slice0, slice_step, slice_lds_step);
+        for (int u = 0; u < KS; ++u) rq.issue(u, k_slice0, slice_step, slice_lds_step);
     }
 
-    // ---- Q rows of this wave as B operands: 8 k-steps of 16 along d ----
-    bf16x8_t q_reg[8];
+    // ---- Q rows of this wave as B operands: KS k-steps of 16 along d ----
+    bf16x8_t q_reg[KS];
     {
         const uint16_t* src = q + (int64_t)tok_q * q_st + (int64_t)h * q_sh + hi * 8;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
+        for (int ks = 0; ks < KS; ++ks) {
             uint4 x = make_uint4(0u, 0u, 0u, 0u);
             if (q_valid) x = *reinterpret_cast<const uint4*>(src + ks * 16);
             q_reg[ks] = as_bf16x8(x);
         }
     }
 
-    f32x16_t o_acc[4];
+    f32x16_t o_acc[DT];
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int x = 0; x < 16; ++x) o_acc[dt][x] = 0.f;
     const float neg_inf = -__builtin_huge_valf();
@@ -278,22 +328,22 @@ __device__ __forceinline__ void sparse_attn_body(
     // per-lane LDS offsets that do not change between blocks.  Both swizzles are XORs of address
     // bits that are zero in the unswizzled per-lane offset, so the offset of operand n is one
     // v_xor of a per-lane base with a constant, plus an immediate.
-    const int k_row = swap_bits_2_3(col);              // + t*32 ; (row & 15) == (k_row & 15)
-    const uint32_t k_base0 = k_row * kRowBytes + (((k_row & 15) ^ hi) << 4);
+    const int k_row = swap_bits_2_3(col);              // + t*32, which leaves the swizzle term alone
+    const uint32_t k_base0 = k_row * kRowBytes + ((k_swz(k_row) ^ hi) << 4);
     // transposing V read: lane l fetches row key0 + 8*hi + (l%16)/4 (+4), 8 bytes at column
     // dt*32 + 16*((l>>4)&1) + 4*(l&3); the 64-byte group index dt is XORed with (row & 3)
-    const int v_row = hi * 8 + ((lane & 15) >> 2);     // key0 and the +4 keep (row & 3)
-    const uint32_t v_base0 = v_row * kRowBytes + ((v_row & 3) << 6) + (((lane >> 4) & 1) << 5) + ((lane & 3) << 3);
+    const int v_row = hi * 8 + ((lane & 15) >> 2);     // key0 and the +4 leave the swizzle term alone
+    const uint32_t v_base0 = v_row * kRowBytes + (v_swz(v_row) << 4) + (((lane >> 4) & 1) << 5) + ((lane & 3) << 3);
     uint32_t k_base = k_base0, v_base = v_base0;
 
-    // Operand n of S^T (matrix instruction n: key tile n/8, 16-wide step n%8 along d; the lane's
-    // 16-byte chunk is 2*(n%8) + hi) and of O^T (matrix instruction n: 16-key step n/4, d tile n%4).
+    // Operand n of S^T (matrix instruction n: key tile n/KS, 16-wide step n%KS along d; the lane's
+    // 16-byte chunk is 2*(n%KS) + hi) and of O^T (matrix instruction n: 16-key step n/DT, d tile n%DT).
     auto load_k = [&](int n) {
-        const int t = n >> 3;
-        return *reinterpret_cast<const uint4*>(k_lds + (k_base ^ ((n & 7) << 5)) + t * 32 * kRowBytes);
+        const int t = n / KS, ks = n % KS;
+        return *reinterpret_cast<const uint4*>(k_lds + (k_base ^ (ks << 5)) + t * 32 * kRowBytes);
     };
     auto load_v = [&](int n) {
-        const int step = n >> 2, dt = n & 3;
+        const int step = n / DT, dt = n % DT;
         const unsigned char* p0 = v_lds + (v_base ^ (dt << 6)) + step * 16 * kRowBytes;
         const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)p0);
         const s16x4_t up = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p0 + 4 * kRowBytes));
@@ -309,9 +359,9 @@ __device__ __forceinline__ void sparse_attn_body(
     // The softmax of a block is 8*KT accumulator pairs per lane.  Vector and matrix instructions
     // of the SAME wave overlap well, those of two waves sharing a SIMD do not, so the pairs are
     // spread over the wave's own matrix instructions (SoftmaxSchedule).
-    using Sched = SoftmaxSchedule<KT>;
+    using Sched = SoftmaxSchedule<KT, KS>;
     constexpr int NS = Sched::NS, kChecks = Sched::kChecks;
-    auto pairs_by = [](int slot) { return Sched::pairs_by(slot); };
+    auto pairs_by = [](int slot) { return Sched::kTable.v[slot + 1]; };
     constexpr int kCheckSlot[3] = {Sched::check_slot(0), Sched::check_slot(1), Sched::check_slot(2)};
 
     f32x16_t s_acc[KT];
@@ -335,8 +385,9 @@ __device__ __forceinline__ void sparse_attn_body(
         p_pk[t][q & 7] = pk;
         ps[q & 3] = sum;
     };
-    auto softmax_slot = [&](int slot) {                // at most one pair per slot
-        if (pairs_by(slot) > pairs_by(slot - 1)) softmax_pair(pairs_by(slot - 1));
+    auto softmax_slot = [&](int slot) {                // one pair per slot at most (two at d = 64)
+#pragma unroll
+        for (int q = pairs_by(slot - 1); q < pairs_by(slot); ++q) softmax_pair(q);
     };
     auto window_sum = [&]() { return (ps[0] + ps[1]) + (ps[2] + ps[3]); };
     auto clear_sum = [&]() {
@@ -364,7 +415,7 @@ __device__ __forceinline__ void sparse_attn_body(
             m_ref = mx;
             l_run *= corr;
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
+            for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                 for (int x = 0; x < 16; ++x) o_acc[dt][x] *= corr;
         }
@@ -392,8 +443,8 @@ __device__ __forceinline__ void sparse_attn_body(
             if (t * 32 + 16 * (x >> 3) + (x & 7) > limit) s_acc[t][x] = neg_inf;
     };
 
-    constexpr int kStepsPerRequestV = (NS / 2) / 8;    // V's 8 requests go under the first half of S^T,
-    constexpr int kStepsPerRequestK = NS / 8;          // the next K's under all of O^T
+    constexpr int kStepsPerRequestV = (NS / 2) / KS;   // V's KS requests go under the first half of S^T,
+    constexpr int kStepsPerRequestK = NS / KS;         // the next K's under all of O^T
     const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     for (int it = 0; it < cnt; ++it) {
@@ -422,7 +473,7 @@ __device__ __forceinline__ void sparse_attn_body(
 #pragma unroll
         for (int t = 0; t < KT; ++t) {
 #pragma unroll
-            for (int n = t * 8; n < t * 8 + 8; ++n) {
+            for (int n = t * KS; n < t * KS + KS; ++n) {
                 if ((n & 1) == 0) {
                     if (n + kAhead < NS) ka[(n + kAhead) % kSlots] = load_k(n + kAhead);
                     if (n + kAhead + 1 < NS) ka[(n + kAhead + 1) % kSlots] = load_k(n + kAhead + 1);
@@ -430,8 +481,8 @@ __device__ __forceinline__ void sparse_attn_body(
                 }
                 if (n < NS / 2 && n % kStepsPerRequestV == 0)
                     v_rq.issue(n / kStepsPerRequestV, v_slice0, slice_step, slice_lds_step);
-                s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[n % kSlots]), q_reg[n & 7],
-                                                                  (n & 7) == 0 ? zero16 : s_acc[t], 0, 0, 0);
+                s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[n % kSlots]), q_reg[n % KS],
+                                                                  (n % KS) == 0 ? zero16 : s_acc[t], 0, 0, 0);
                 softmax_slot(n);
                 STEM_SCHED_FENCE();
             }
@@ -458,7 +509,7 @@ __device__ __forceinline__ void sparse_attn_body(
                     if (n + kAhead < NS) va[(n + kAhead) % kSlots] = load_v(n + kAhead);
                 }
                 if (n % kStepsPerRequestK == 1) k_rq.issue(n / kStepsPerRequestK, k_slice0, slice_step, slice_lds_step);
-                const int g2 = n >> 2, t = g2 >> 1, u = g2 & 1, dt = n & 3;
+                const int g2 = n / DT, t = g2 >> 1, u = g2 & 1, dt = n % DT;
                 const uint4 pb = make_uint4(p_pk[t][u * 4], p_pk[t][u * 4 + 1], p_pk[t][u * 4 + 2], p_pk[t][u * 4 + 3]);
                 o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[n % kSlots]), as_bf16x8(pb),
                                                                    o_acc[dt], 0, 0, 0);
@@ -490,9 +541,9 @@ __device__ __forceinline__ void sparse_attn_body(
     // A lane holds four columns of every group of eight (the other four sit in lane ^ 32).  Two
     // groups at a time, one half-wave swap per packed register gives each lane eight consecutive
     // columns, i.e. 16-byte stores.  (The swap runs in every lane, valid query or not.)
-    uint4 packed[4][2];
+    uint4 packed[DT][2];
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int m = 0; m < 2; ++m) {
             const int xa = m * 8, xb = m * 8 + 4;      // accumulators of groups 2m and 2m+1
@@ -507,7 +558,7 @@ __device__ __forceinline__ void sparse_attn_body(
     if (q_valid) {
         uint16_t* dst = out + (int64_t)tok_q * q_st + (int64_t)h * q_sh + hi * 8;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int m = 0; m < 2; ++m) *reinterpret_cast<uint4*>(dst + dt * 32 + m * 16) = packed[dt][m];
         if (lse != nullptr && hi == 0)
@@ -515,31 +566,28 @@ __device__ __forceinline__ void sparse_attn_body(
     }
 }
 
-template <int B>
-__global__ __launch_bounds__(B * 2, 2) void sparse_attn_kernel(
+template <int B, int D>
+__global__ __launch_bounds__(B * 2, D == 256 ? 1 : 2) void sparse_attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ counts, const int32_t* __restrict__ indices,
     uint16_t* __restrict__ out, float* __restrict__ lse, SeqTable seq, int Hq, int R, int G, int T,
     int kmax, bool shared_lists, int64_t q_st, int64_t q_sh, int64_t kv_st, int64_t kv_sh, float scale,
     int items_per_xcd, int xcds_per_kv_head) {
-    __shared__ __attribute__((aligned(1024))) unsigned char k_lds[B * kRowBytes];
-    __shared__ __attribute__((aligned(1024))) unsigned char v_lds[B * kRowBytes];
-    sparse_attn_body<B>(q, k, v, counts, indices, out, lse, seq, Hq, R, G, T, kmax, shared_lists, q_st, q_sh,
-                        kv_st, kv_sh, scale, items_per_xcd, xcds_per_kv_head, k_lds, v_lds);
+    __shared__ __attribute__((aligned(1024))) unsigned char k_lds[B * D * 2];
+    __shared__ __attribute__((aligned(1024))) unsigned char v_lds[B * D * 2];
+    sparse_attn_body<B, D>(q, k, v, counts, indices, out, lse, seq, Hq, R, G, T, kmax, shared_lists, q_st, q_sh,
+                           kv_st, kv_sh, scale, items_per_xcd, xcds_per_kv_head, k_lds, v_lds);
 }
 
 int launch_sparse_attn(const Problem& p, const void* q, const void* k, const void* v,
                        const int32_t* counts, const int32_t* indices, int32_t kmax,
                        bool lists_per_kv_head, float softmax_scale, void* out, float* lse,
                        hipStream_t stream) {
-    if (p.d != kHeadDim)
-        return launch_sparse_attn_generic(p, q, k, v, counts, indices, kmax, lists_per_kv_head, softmax_scale,
-                                          out, lse, stream);
     // the block requests address one sequence of one KV head through a 32-bit byte offset, with
     // offsets from 2^31 on reserved for requests that must fetch nothing
     for (int s = 0; s < p.batch; ++s) {
         const int64_t rows = p.seq.tok_start[s + 1] - p.seq.tok_start[s];
-        if (rows > 0 && (rows - 1) * p.kv_st * 2 + kHeadDim * 2 > 0x7fffffffll) return STEM_ERR_UNSUPPORTED;
+        if (rows > 0 && (rows - 1) * p.kv_st * 2 + p.d * 2 > 0x7fffffffll) return STEM_ERR_UNSUPPORTED;
     }
     const int64_t items = (int64_t)p.Hq * p.R;
     const int xcds_per_kv_head = (p.Hkv <= 8 && 8 % p.Hkv == 0) ? 8 / p.Hkv : 0;
@@ -547,19 +595,23 @@ int launch_sparse_attn(const Problem& p, const void* q, const void* k, const voi
                                 ? (int64_t)((p.R + xcds_per_kv_head - 1) / xcds_per_kv_head) * p.G
                                 : (items + 7) / 8;
     if (per_xcd * 8 > 0x7fffffff) return STEM_ERR_UNSUPPORTED;
-    dim3 grid((unsigned)(per_xcd * 8));
+    dim3 grid((unsigned)(per_xcd * 8)), block(p.B * 2);
     const uint16_t* qq = static_cast<const uint16_t*>(q);
     const uint16_t* kk = static_cast<const uint16_t*>(k);
     const uint16_t* vv = static_cast<const uint16_t*>(v);
     uint16_t* oo = static_cast<uint16_t*>(out);
-    if (p.B == 128)
-        hipLaunchKernelGGL(sparse_attn_kernel<128>, grid, dim3(256), 0, stream, qq, kk, vv, counts,
-                           indices, oo, lse, p.seq, p.Hq, p.R, p.G, p.T, kmax, lists_per_kv_head, p.q_st, p.q_sh,
-                           p.kv_st, p.kv_sh, softmax_scale, (int)per_xcd, xcds_per_kv_head);
-    else
-        hipLaunchKernelGGL(sparse_attn_kernel<64>, grid, dim3(128), 0, stream, qq, kk, vv, counts,
-                           indices, oo, lse, p.seq, p.Hq, p.R, p.G, p.T, kmax, lists_per_kv_head, p.q_st, p.q_sh,
-                           p.kv_st, p.kv_sh, softmax_scale, (int)per_xcd, xcds_per_kv_head);
+#define STEM_ATTN_LAUNCH(BB, DD)                                                                          \
+    hipLaunchKernelGGL((sparse_attn_kernel<BB, DD>), grid, block, 0, stream, qq, kk, vv, counts, indices, \
+                       oo, lse, p.seq, p.Hq, p.R, p.G, p.T, kmax, lists_per_kv_head, p.q_st, p.q_sh,      \
+                       p.kv_st, p.kv_sh, softmax_scale, (int)per_xcd, xcds_per_kv_head)
+    if (p.B == 128 && p.d == 128) STEM_ATTN_LAUNCH(128, 128);
+    else if (p.B == 64 && p.d == 128) STEM_ATTN_LAUNCH(64, 128);
+    else if (p.B == 128 && p.d == 64) STEM_ATTN_LAUNCH(128, 64);
+    else if (p.B == 64 && p.d == 64) STEM_ATTN_LAUNCH(64, 64);
+    else if (p.B == 128 && p.d == 256) STEM_ATTN_LAUNCH(128, 256);
+    else if (p.B == 64 && p.d == 256) STEM_ATTN_LAUNCH(64, 256);
+    else return STEM_ERR_UNSUPPORTED;
+#undef STEM_ATTN_LAUNCH
     return check_launch();
 }
 

@@ -58,15 +58,10 @@ int launch_score_select(const Problem& p, int ad_stride, const float* q_bar, con
                         const float* m_v, float beta, float route_scale, const int32_t* budget,
                         int32_t n_sink, int32_t n_local, int32_t* counts, int32_t* indices,
                         int32_t kmax, float* debug_scores, hipStream_t stream);
-// head size 128 runs the tuned kernel, 64 and 256 go on to launch_sparse_attn_generic
 int launch_sparse_attn(const Problem& p, const void* q, const void* k, const void* v,
                        const int32_t* counts, const int32_t* indices, int32_t kmax,
                        bool lists_per_kv_head, float softmax_scale, void* out, float* lse,
                        hipStream_t stream);
-int launch_sparse_attn_generic(const Problem& p, const void* q, const void* k, const void* v,
-                               const int32_t* counts, const int32_t* indices, int32_t kmax,
-                               bool lists_per_kv_head, float softmax_scale, void* out, float* lse,
-                               hipStream_t stream);
 
 inline int check_launch() {
     return hipGetLastError() == hipSuccess ? STEM_OK : STEM_ERR_HIP;
