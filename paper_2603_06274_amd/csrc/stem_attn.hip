@@ -21,12 +21,12 @@
 //
 // Inside a wave the instruction stream is kept dense around the matrix instructions: LDS operands
 // are read six matrix instructions ahead into a ring of registers, the softmax of a block is
-// spread pair by pair over the wave's own matrix instructions (S^T tiles 1..3 and the first three
-// quarters of O^T), and the softmax runs without a running maximum: a per-query reference is set
+// spread pair by pair over the wave's own matrix instructions (the eight pairs of a 32-key tile
+// under the matrix instructions that follow the tile), and the softmax runs without a running
+// maximum: a per-query reference is set
 // on the first block and moved only when a window of probabilities overflows (slow path).
 //
-// The kernel is a template over the block size B (64, 128) and the head size D (64, 128, 256); the
-// headline shape (128, 128) has its own hand-placed softmax schedule, the others a generic one.
+// The kernel is a template over the block size B (64, 128) and the head size D (64, 128, 256).
 //
 // LDS layouts (rows of 2 D bytes, unpadded: the direct loads write 1 KiB contiguously): K has its
 // 16-byte chunks XORed with (row & 15), so the 16 rows a quarter-wave reads one chunk of spread
@@ -130,26 +130,18 @@ struct SoftmaxSchedule {
     static constexpr int NS = KT * KS;                 // matrix instructions per product and block
     static constexpr int DT = KS / 2;                  // matrix instructions per 16-key step of O^T
     static constexpr int NP = KT * 8;                  // accumulator pairs per block and lane
-    static constexpr bool kTuned = KT == 4 && KS == 8; // the headline shape has a schedule of its own
-    static constexpr int kChecks = kTuned ? 3 : 2;
+    static constexpr int kChecks = 2;
     static constexpr int kMaxPerSlot = KS < 8 ? 2 : 1;
-    // Generic: a check when O^T starts (tiles 0 .. KT-2 issued, nothing consumed) and one when O^T
-    // reaches the last tile (its pairs issued, all others consumed).
-    static constexpr int check_slot(int c) {
-        if (kTuned) return c == 0 ? NS : c == 1 ? 48 : 56;
-        return c == 0 ? NS : NS + KS * (KT - 1);
-    }
-    // slot after whose matrix instruction pair q is issued, generic rule: the eight pairs of tile t
-    // spread over the KS slots that follow the tile's completion
+    // The reference is checked when O^T starts (tiles 0 .. KT-2 issued, nothing consumed) and when
+    // O^T reaches the last tile (its pairs issued, all others consumed).
+    static constexpr int check_slot(int c) { return c == 0 ? NS : NS + KS * (KT - 1); }
+    // slot after whose matrix instruction pair q is issued: the eight pairs of tile t are spread over
+    // the KS slots that follow the tile's completion
     static constexpr int issue_slot(int q) { return (q / 8 + 1) * KS + ((q % 8) * KS) / 8; }
-    // pairs issued once slot `slot` is issued.  Headline shape: tiles 0..2 at two pairs per three
-    // slots from slot 8 on, tile 3 one per slot from slot 48 on.
+    // slot of the O^T instruction that first consumes pair q
+    static constexpr int use_slot(int q) { return NS + DT * (2 * (q / 8) + (q % 8) / 4); }
+    // pairs issued once slot `slot` is issued
     static constexpr int pairs_by(int slot) {
-        if (kTuned) {
-            if (slot < 8) return 0;
-            if (slot < 48) return ((slot - 7) * 2) / 3 > 24 ? 24 : ((slot - 7) * 2) / 3;
-            return 24 + (slot - 47) > NP ? NP : 24 + (slot - 47);
-        }
         int n = 0;
         for (int q = 0; q < NP; ++q) n += issue_slot(q) <= slot ? 1 : 0;
         return n;
@@ -159,9 +151,8 @@ struct SoftmaxSchedule {
             const int before = s == 0 ? 0 : pairs_by(s - 1), now = pairs_by(s);
             if (now < before || now > before + kMaxPerSlot) return false;
             for (int q = before; q < now; ++q) {
-                const int t = q / 8;
-                if (s <= KS * t + KS - 1) return false;                      // its S^T tile is complete
-                if (s >= NS + DT * (2 * t + (q % 8) / 4)) return false;      // O^T has not reached it
+                if (s <= KS * (q / 8) + KS - 1) return false;                // its S^T tile is complete
+                if (s >= use_slot(q)) return false;                          // O^T has not reached it
             }
         }
         int lo = 0;
@@ -169,6 +160,8 @@ struct SoftmaxSchedule {
             const int slot = check_slot(c);
             if (slot < NS || slot % DT) return false;
             if (lo > 4 * ((slot - NS) / DT)) return false;   // pairs below the window are consumed (4 per step)
+            for (int q = lo; q < pairs_by(slot - 1); ++q)
+                if (use_slot(q) < slot) return false;        // pairs of the window are not consumed yet
             lo = pairs_by(slot - 1);
         }
         return lo == NP && pairs_by(2 * NS - 1) == NP;
@@ -360,9 +353,9 @@ __device__ __forceinline__ void sparse_attn_body(
     // of the SAME wave overlap well, those of two waves sharing a SIMD do not, so the pairs are
     // spread over the wave's own matrix instructions (SoftmaxSchedule).
     using Sched = SoftmaxSchedule<KT, KS>;
-    constexpr int NS = Sched::NS, kChecks = Sched::kChecks;
+    constexpr int NS = Sched::NS;
     auto pairs_by = [](int slot) { return Sched::kTable.v[slot + 1]; };
-    constexpr int kCheckSlot[3] = {Sched::check_slot(0), Sched::check_slot(1), Sched::check_slot(2)};
+    constexpr int kCheckSlot[2] = {Sched::check_slot(0), Sched::check_slot(1)};
 
     f32x16_t s_acc[KT];
     uint32_t p_pk[KT][8];                              // bf16 pairs: [tile][16-key step * 4 + pair]
@@ -520,13 +513,7 @@ __device__ __forceinline__ void sparse_attn_body(
         check_window(0);
         pv_range(0, kCheckSlot[1] - NS);
         check_window(1);
-        if (kChecks == 3) {
-            pv_range(kCheckSlot[1] - NS, kCheckSlot[2] - NS);
-            check_window(2);
-            pv_range(kCheckSlot[2] - NS, NS);
-        } else {
-            pv_range(kCheckSlot[1] - NS, NS);
-        }
+        pv_range(kCheckSlot[1] - NS, NS);
         j_cur = j_nxt;
     }
     STEM_WAIT_VMCNT(0);                                // no request may outlive the workgroup's LDS
