@@ -256,6 +256,9 @@ __device__ __forceinline__ void sparse_attn_body(
     const int lrow = w * kSliceRows + slice_row;       // row of slice u = 0
     const uint32_t lane_row_off = (uint32_t)(lrow * row_bytes);
     constexpr int kKVariants = D == 256 ? (B == 128 ? 2 : 4) : (D == 128 && B == 64) ? 2 : 1;
+    static_assert(D == 64 ? (NW * kSliceRows) % 16 == 0 : (kKVariants * NW * kSliceRows) % 16 == 0,
+                  "the K swizzle term of slice u repeats with period kKVariants");
+    static_assert((NW * kSliceRows) % 4 == 0, "the V swizzle term does not depend on the slice");
     uint32_t k_off[kKVariants];
 #pragma unroll
     for (int x = 0; x < kKVariants; ++x) k_off[x] = lane_row_off + ((pc ^ k_swz(lrow + x * NW * kSliceRows)) << 4);
