@@ -116,6 +116,8 @@ int stem_workspace_layout(const stem_shape* shape, int32_t ad_stride, size_t* ho
  * included).  n counts the whole sequence also when the call covers a chunk of it (whose rows
  * keep their index i).  mu = 1 gives the uniform top-k control.  Writes host_budget[R] and, if not NULL,
  * the largest entry to *host_kmax.  Requires 0 < mu <= 1, ks >= 0, k_min, n_sink, n_local >= 0.
+ * (n_local = 0 is accepted here as plain arithmetic - rows may then get a budget of 0 - but the
+ * selection entry points require n_local >= 1 and raise such rows to their forced blocks.)
  */
 int stem_budget_schedule(const stem_shape* shape, const double* host_k_start_blocks, double mu,
                          int32_t k_min, int32_t n_sink, int32_t n_local,
@@ -175,6 +177,8 @@ int stem_group_scores(const stem_shape* shape, const float* scores, int32_t redu
  * stem_group_scores), counts [Hkv, R], indices [Hkv, R, kmax]; 0 is the paper's per-head selection.
  * kmax is the row pitch of indices.  It must be at least n_sink + n_local (or at least NBmax), so the
  * forced blocks always fit; a row whose budget exceeds kmax is cut to kmax blocks (k = min(k, kmax)).
+ * n_sink >= 0 and n_local >= 1: the method always keeps the diagonal block, so every list holds
+ * block i and no row comes out empty, whatever the budget array says (STEM_ERR_INVALID_ARG otherwise).
  */
 int stem_select(const stem_shape* shape, const float* scores, const int32_t* budget,
                 int32_t n_sink, int32_t n_local, int32_t lists_per_kv_head, int32_t* counts,

@@ -251,9 +251,13 @@ def sparse_attention_row(q: np.ndarray, k: np.ndarray, v: np.ndarray, seq_lo: in
 
     out[t] = sum_u softmax_u(scale * <Q_t, K_u>) V_u over the tokens u of the listed key blocks
     with u <= t.  Returns (out [n,d] fp64, lse [n] fp64) for the block's n valid query tokens.
+    A query with no visible key (possible only with an empty list, which the selection never
+    emits) gets the empty sums: out = 0 and lse = log 0 = -inf.
     """
     t0 = seq_lo + i * block_size
     t1 = min(t0 + block_size, seq_hi)
+    if len(blocks) == 0:
+        return np.zeros((t1 - t0, q.shape[2])), np.full(t1 - t0, NEG_INF)
     key_tok = np.concatenate([
         np.arange(seq_lo + j * block_size, min(seq_lo + (j + 1) * block_size, seq_hi))
         for j in blocks])

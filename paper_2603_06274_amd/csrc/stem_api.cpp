@@ -259,7 +259,8 @@ int stem_estimate_select(const stem_shape* shape, const void* q, const void* k, 
     if ((st = check_ad_stride(p, ad_stride)) != STEM_OK) return st;
     if (!budget || !counts || !indices) return STEM_ERR_INVALID_ARG;
     if (debug_scores && !aligned16(debug_scores)) return STEM_ERR_INVALID_ARG;
-    if (n_sink < 0 || n_local < 0 || kmax < 1) return STEM_ERR_INVALID_ARG;
+    // the diagonal block is always kept (Algorithm 1 step 3c), so the local window holds at least it
+    if (n_sink < 0 || n_local < 1 || kmax < 1) return STEM_ERR_INVALID_ARG;
     if ((int64_t)kmax < (int64_t)n_sink + n_local && kmax < p.NBmax) return STEM_ERR_INVALID_ARG;
     st = stem_pool(shape, q, k, v, ad_stride, workspace, workspace_bytes, hip_stream);
     if (st != STEM_OK || p.R == 0) return st;
@@ -291,7 +292,8 @@ int stem_select(const stem_shape* shape, const float* scores, const int32_t* bud
     if (st != STEM_OK) return st;
     if (lists_per_kv_head != 0 && lists_per_kv_head != 1) return STEM_ERR_INVALID_ARG;
     if (!scores || !budget || !counts || !indices) return STEM_ERR_INVALID_ARG;
-    if (n_sink < 0 || n_local < 0 || kmax < 1) return STEM_ERR_INVALID_ARG;
+    // the diagonal block is always kept (Algorithm 1 step 3c), so the local window holds at least it
+    if (n_sink < 0 || n_local < 1 || kmax < 1) return STEM_ERR_INVALID_ARG;
     if ((int64_t)kmax < (int64_t)n_sink + n_local && kmax < p.NBmax) return STEM_ERR_INVALID_ARG;
     if (p.R == 0) return STEM_OK;
     return launch_select(p, lists_per_kv_head ? p.Hkv : p.Hq, scores, budget, n_sink, n_local, counts,
@@ -309,6 +311,12 @@ int stem_sparse_attn(const stem_shape* shape, const void* q, const void* k, cons
     if ((st = check_qkv(q, k, v)) != STEM_OK) return st;
     if (!counts || !indices || !out || !aligned16(out) || kmax < 1) return STEM_ERR_INVALID_ARG;
     if (!std::isfinite(softmax_scale) || !(softmax_scale > 0.f)) return STEM_ERR_INVALID_ARG;
+    // the kernel addresses one sequence of one KV head through a 32-bit byte offset, with offsets
+    // from 2^31 on reserved for requests that must fetch nothing
+    for (int s = 0; s < p.batch; ++s) {
+        const int64_t rows = p.seq.tok_start[s + 1] - p.seq.tok_start[s];
+        if (rows > 0 && (rows - 1) * p.kv_st * 2 + p.d * 2 > 0x7fffffffll) return STEM_ERR_UNSUPPORTED;
+    }
     if (p.R == 0) return STEM_OK;
     return launch_sparse_attn(p, q, k, v, counts, indices, kmax, lists_per_kv_head != 0, softmax_scale,
                               out, lse, static_cast<hipStream_t>(hip_stream));

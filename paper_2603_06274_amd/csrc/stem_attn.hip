@@ -573,12 +573,8 @@ int launch_sparse_attn(const Problem& p, const void* q, const void* k, const voi
                        const int32_t* counts, const int32_t* indices, int32_t kmax,
                        bool lists_per_kv_head, float softmax_scale, void* out, float* lse,
                        hipStream_t stream) {
-    // the block requests address one sequence of one KV head through a 32-bit byte offset, with
-    // offsets from 2^31 on reserved for requests that must fetch nothing
-    for (int s = 0; s < p.batch; ++s) {
-        const int64_t rows = p.seq.tok_start[s + 1] - p.seq.tok_start[s];
-        if (rows > 0 && (rows - 1) * p.kv_st * 2 + p.d * 2 > 0x7fffffffll) return STEM_ERR_UNSUPPORTED;
-    }
+    // (the host entry point has checked that one sequence of one KV head spans less than 2 GiB: the
+    // block requests use a 32-bit byte offset, with offsets from 2^31 on reserved for "fetch nothing")
     const int64_t items = (int64_t)p.Hq * p.R;
     const int xcds_per_kv_head = (p.Hkv <= 8 && 8 % p.Hkv == 0) ? 8 / p.Hkv : 0;
     const int64_t per_xcd = xcds_per_kv_head > 0

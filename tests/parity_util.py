@@ -5,10 +5,15 @@ Bars (the benchmark spec):
   block scores   |gpu - oracle| <= 1e-4 * max(|oracle|, rms of the oracle row)
   index lists    bit-exact, except rows whose differing entries all sit within 1e-5 (relative) of the
                  oracle's selection threshold; those rows are counted and printed
-  output         max-abs 1.5e-2 and relative L2 5e-3 against the fp64 oracle.  The output is stored in
-                 bf16, whose rounding alone costs up to half an ulp = 2^-8 |o|; that exceeds 1.5e-2
-                 once |o| > 3.84 (value rows scaled x4 reach |o| ~ 10), so the max-abs bar is applied
-                 to |gpu - oracle| - 2^-8 |oracle|.  The raw figure is returned and printed too.
+  output         max-abs 1.5e-2 and relative L2 5e-3 against the fp64 oracle, taken literally on every
+                 entry where the bar can be met at all: the output is stored in bf16, whose rounding
+                 alone costs up to half an ulp <= 2^-8 |o|, and that exceeds 1.5e-2 only once
+                 |o| > 3.84 (value rows scaled x4 reach |o| ~ 10).  So |gpu - oracle| <= 1.5e-2 where
+                 |oracle| <= 3.84, and |gpu - oracle| - 2^-8 |oracle| <= 1.5e-2 above that.  The same
+                 comparison is made after rounding the oracle to bf16 (one bf16 ulp of allowance above
+                 3.84 instead of half); all figures are returned and printed.
+  lse            5e-3 absolute where the row sum is taken over the bf16-rounded probabilities (each
+                 within 2^-8 relative of the fp32 one), which is what the library header promises
 """
 from __future__ import annotations
 
@@ -112,35 +117,99 @@ def check_lists(w: wl.Workload, g_counts, g_idx, o_counts, o_idx, o_scores, log=
     return same
 
 
-def check_output(g_out, o_out: np.ndarray, what=""):
+OUT_EXACT_BAR_LIMIT = 3.84      # above this half a bf16 ulp alone can exceed OUT_MAX_ABS
+LSE_ABS = 5e-3
+
+
+def check_output(g_out, o_out: np.ndarray, what="", log=None):
     """g_out: the GPU output [T,Hq,d] (torch tensor, any device) ; o_out: the oracle's fp64 array of the
-    same shape, NaN where the oracle was not asked to compute (those entries are skipped)."""
+    same shape, NaN where the oracle was not asked to compute (those entries are skipped).
+
+    Returns (max_abs, rel_l2) against the fp64 oracle; the other figures go to `log`."""
     sel = ~np.isnan(o_out[..., 0])
     assert sel.any()
     g = g_out.detach().cpu()[torch.from_numpy(sel)].double().numpy()
-    o = o_out[sel]
+    return check_output_arrays(g, o_out[sel], what, log)
+
+
+def check_output_arrays(g: np.ndarray, o: np.ndarray, what="", log=None):
+    """The output bars on two equally shaped fp64 arrays: g from the GPU (bf16 values), o the oracle."""
     assert not np.isnan(g).any(), "NaN in GPU output"
-    d = g - o
-    max_abs = float(np.abs(d).max())
-    beyond_rounding = float((np.abs(d) - np.abs(o) * 2.0 ** -8).max())
+    d = np.abs(g - o)
+    small = np.abs(o) <= OUT_EXACT_BAR_LIMIT
+    max_abs = float(d.max())
+    max_abs_small = float(d[small].max()) if small.any() else 0.0
+    beyond_rounding = float((d - np.abs(o) * 2.0 ** -8)[~small].max()) if (~small).any() else 0.0
     rel_l2 = float(np.sqrt((d * d).sum() / max((o * o).sum(), 1e-300)))
-    assert beyond_rounding <= OUT_MAX_ABS, "%s max-abs %.4g (%.4g beyond bf16 rounding)" % (what, max_abs, beyond_rounding)
-    assert rel_l2 <= OUT_REL_L2, "%s rel-L2 %.4g" % (what, rel_l2)
+    # the same after rounding the oracle to the output's storage type
+    o_bf = torch.from_numpy(o).to(torch.bfloat16).double().numpy()
+    d_bf = np.abs(g - o_bf)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(o_bf), 2.0 ** -126))) - 7)
+    max_abs_bf_small = float(d_bf[small].max()) if small.any() else 0.0
+    beyond_ulp = float((d_bf - ulp)[~small].max()) if (~small).any() else 0.0
+    rel_l2_bf = float(np.sqrt((d_bf * d_bf).sum() / max((o_bf * o_bf).sum(), 1e-300)))
+    msg = ("%s output vs fp64 oracle: max-abs %.4g (%.4g where |o| <= %.2f, %.4g beyond bf16 rounding above), "
+           "rel-L2 %.4g; vs bf16-rounded oracle: max-abs %.4g where |o| <= %.2f, %.4g beyond one ulp above, "
+           "rel-L2 %.4g; %d of %d entries above %.2f"
+           % (what, max_abs, max_abs_small, OUT_EXACT_BAR_LIMIT, beyond_rounding, rel_l2, max_abs_bf_small,
+              OUT_EXACT_BAR_LIMIT, beyond_ulp, rel_l2_bf, int((~small).sum()), small.size, OUT_EXACT_BAR_LIMIT))
+    (log or print)(msg)
+    assert max_abs_small <= OUT_MAX_ABS, msg
+    assert beyond_rounding <= OUT_MAX_ABS, msg
+    assert max_abs_bf_small <= OUT_MAX_ABS, msg
+    assert beyond_ulp <= OUT_MAX_ABS, msg
+    assert rel_l2 <= OUT_REL_L2 and rel_l2_bf <= OUT_REL_L2, msg
     return max_abs, rel_l2
 
 
-def sample_rows(w: wl.Workload, n_random: int, seed: int):
-    """Global rows to check at full size: per sequence the first two, the last two, the rows around
-    the end of the causal ramp (k_start), plus random ones."""
+def check_lse(g_lse, o_lse: np.ndarray, what=""):
+    """g_lse: GPU lse [Hq,T] (torch tensor); o_lse: oracle fp64, NaN where not computed; -inf must
+    match exactly (a query with no visible key)."""
+    m = ~np.isnan(o_lse)
+    g = g_lse.detach().cpu().double().numpy()[m]
+    o = o_lse[m]
+    inf = np.isneginf(o)
+    assert np.array_equal(np.isneginf(g), inf), "%s: -inf pattern of lse differs" % what
+    err = float(np.abs(g[~inf] - o[~inf]).max()) if (~inf).any() else 0.0
+    assert err <= LSE_ABS, "%s lse error %.4g" % (what, err)
+    return err
+
+
+def stratified_pairs(w: wl.Workload, random_per_head: int, seed: int):
+    """(head, global query-block row) pairs to check at full size: for EVERY head and every packed
+    sequence the first two rows, the rows around the end of the causal ramp (where the budget stops
+    being clamped by causality), the last two rows, plus random rows per head.  The fixed rows hold
+    both row parities, so with two XCDs per KV head (which take alternate rows) every head is seen
+    on both of its XCDs; with one XCD per KV head every head means every XCD."""
     r = np.random.default_rng(seed)
-    rows = set()
-    row0 = 0
-    for s, nb in enumerate(w.blocks_per_seq):
-        ks = int(w.k_start_blocks[s])
-        for i in (0, 1, ks - 1, ks, ks + 1, nb - 2, nb - 1):
-            if 0 <= i < nb:
-                rows.add(row0 + i)
-        row0 += nb
+    pairs = []
     total = w.total_rows
-    rows.update(int(x) for x in r.choice(total, size=min(n_random, total), replace=False))
-    return sorted(rows)
+    for h in range(w.num_q_heads):
+        rows = set()
+        row0 = 0
+        for s, nb in enumerate(w.blocks_per_seq):
+            ks = int(w.k_start_blocks[s])
+            for i in (0, 1, ks - 1, ks, ks + 1, nb - 2, nb - 1):
+                if 0 <= i < nb:
+                    rows.add(row0 + i)
+            row0 += nb
+        rows.update(int(x) for x in r.choice(total, size=min(random_per_head, total), replace=False))
+        pairs += [(h, x) for x in sorted(rows)]
+    return pairs
+
+
+def oracle_attention_pairs(w: wl.Workload, qkv, counts, indices, pairs):
+    """Oracle stage 3 for (head, global row) pairs, one by one.  Returns a list of
+    (head, row, first token, one past the last token, out [n,d] fp64, lse [n] fp64)."""
+    q, k, v = qkv
+    G = w.num_q_heads // w.num_kv_heads
+    tab = so.sequence_table(w.cu_seqlens, w.block_size)
+    res = []
+    for h, r in pairs:
+        lo, hi, nb, row0 = next(t for t in tab if t[3] <= r < t[3] + t[2])
+        i = r - row0
+        o, l = so.sparse_attention_row(q, k, v, lo, hi, w.block_size, i, h, h // G,
+                                       indices[h, r, :counts[h, r]], w.softmax_scale)
+        t0 = lo + i * w.block_size
+        res.append((h, r, t0, t0 + o.shape[0], o, l))
+    return res

@@ -1,10 +1,12 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
 Stages 1 and 2 are compared in full (every pooled vector, every score, every list).  Stage 3 is
-compared on sampled (head, query-block row) pairs the oracle computes one by one: the first and last
-rows of every sequence, the rows around the end of the causal ramp, and random rows.  Invariants that
-hold at any size are checked on the whole output: no NaN, and the first token of every sequence
-returns its own value row.
+compared in full where the oracle can do the whole layer (32K), and otherwise on several hundred
+(head, query-block row) pairs the oracle computes one by one, stratified over every head (hence
+every XCD and both halves of a KV head that two XCDs share), every packed sequence, both ends of
+the causal ramp and the last rows, plus random rows.  Parity of stage 3 is claimed for those rows.
+On the whole output: it is NaN before the run and free of NaN after it (every workgroup wrote its
+rows), and the first token of every sequence returns its own value row.
 """
 import numpy as np
 import pytest
@@ -43,10 +45,12 @@ def uniform_control(w):
     return wl.with_budget(w, [k_uni], 1.0, "_uniform"), target, total(k_uni, 1.0)
 
 
-def full_size_case(w, n_random_rows, heads):
+def full_size_case(w, random_rows_per_head, whole_output=False, heads=None):
     say("case", w.name, "seed", w.seed, "T", w.total_tokens, "ks", w.k_start_blocks, "mu", w.mu)
     data, qkv = tensors_for(w)
     pf = pu.device_prefill(w, data)
+    pf.out.fill_(float("nan"))
+    pf.lse.fill_(float("nan"))
     pf.run()
     torch.cuda.synchronize()
     q_bar, k_bar, m_v, scores = pu.oracle_estimate(w, qkv)
@@ -58,50 +62,62 @@ def full_size_case(w, n_random_rows, heads):
     err = pu.check_scores(pf.scores.cpu().numpy(), scores)
     same = pu.check_lists(w, pf.counts.cpu().numpy(), pf.indices.cpu().numpy(), counts, indices, scores, say)
     assert same.mean() > 0.99
+    say(w.name, "stages 1-2 agree; stage 3 ...")
 
-    rows = pu.sample_rows(w, n_random_rows, seed=w.seed + 100)
-    o_out, o_lse = so.sparse_attention(*qkv, w.cu_seqlens, w.block_size, counts, indices, w.softmax_scale,
-                                       heads=heads, rows=rows)
-    B = w.block_size
-    for (lo, hi, nb, row0) in so.sequence_table(w.cu_seqlens, B):
-        for i in range(nb):
-            for h in heads:
-                if not same[h, row0 + i]:
-                    o_out[lo + i * B:min(lo + (i + 1) * B, hi), h] = np.nan
-    max_abs, rel_l2 = pu.check_output(pf.out, o_out, w.name)
-    m = ~np.isnan(o_lse)
-    assert np.abs(pf.lse.cpu().numpy()[m] - o_lse[m]).max() <= 5e-3
+    g_out, g_lse = pf.out.cpu(), pf.lse.cpu()
     # whole-output invariants
-    assert not torch.isnan(pf.out).any().item()
+    assert not torch.isnan(g_out).any().item() and not torch.isnan(g_lse).any().item()
     G = w.num_q_heads // w.num_kv_heads
     for s in range(len(w.seq_lens)):
         if w.seq_lens[s]:
             t0 = w.cu_seqlens[s]
-            assert torch.equal(pf.out[t0].cpu(), data["v"][t0].repeat_interleave(G, dim=0))
-    say("%s: density %.4f, score err %.3g, %d sampled rows x %d heads: max-abs %.4g rel-L2 %.4g"
-        % (w.name, density, err, len(rows), len(heads), max_abs, rel_l2))
+            assert torch.equal(g_out[t0], data["v"][t0].repeat_interleave(G, dim=0))
+    B = w.block_size
+    if whole_output:
+        o_out, o_lse = so.sparse_attention(*qkv, w.cu_seqlens, w.block_size, counts, indices, w.softmax_scale)
+        for (lo, hi, nb, row0) in so.sequence_table(w.cu_seqlens, B):
+            for h, r in np.argwhere(~same[:, row0:row0 + nb]):
+                o_out[lo + r * B:min(lo + (r + 1) * B, hi), h] = np.nan
+                o_lse[h, lo + r * B:min(lo + (r + 1) * B, hi)] = np.nan
+        max_abs, rel_l2 = pu.check_output(g_out, o_out, w.name, say)
+        lse_err = pu.check_lse(g_lse, o_lse, w.name)
+        n_pairs = int(same.sum())
+    else:
+        pairs = [(h, r) for h, r in pu.stratified_pairs(w, random_rows_per_head, seed=w.seed + 100)
+                 if same[h, r] and (heads is None or h in heads)]
+        res = pu.oracle_attention_pairs(w, qkv, counts, indices, pairs)
+        g = np.concatenate([g_out[t0:t1, h].double().numpy() for h, r, t0, t1, o, l in res])
+        o = np.concatenate([o for h, r, t0, t1, o, l in res])
+        max_abs, rel_l2 = pu.check_output_arrays(g, o, w.name, say)
+        gl = np.concatenate([g_lse[h, t0:t1].double().numpy() for h, r, t0, t1, o, l in res])
+        ol = np.concatenate([l for h, r, t0, t1, o, l in res])
+        lse_err = float(np.abs(gl - ol).max())
+        assert lse_err <= pu.LSE_ABS
+        n_pairs = len(pairs)
+    say("%s: density %.4f, score err %.3g, %d (head, row) pairs%s: max-abs %.4g rel-L2 %.4g lse err %.3g"
+        % (w.name, density, err, n_pairs, " = the whole output" if whole_output else "", max_abs, rel_l2, lse_err))
     del pf
     torch.cuda.empty_cache()
 
 
 def test_llama_32k():
-    full_size_case(wl.LLAMA_32K, 24, heads=[0, 5, 14, 31])
+    full_size_case(wl.LLAMA_32K, 0, whole_output=True)       # all 32 heads x 256 rows
 
 
 def test_llama_128k_headline():
-    full_size_case(wl.LLAMA_128K, 16, heads=[0, 9, 22, 31])
+    full_size_case(wl.LLAMA_128K, 9)                         # 32 heads x ~16 rows
 
 
 @pytest.mark.parametrize("d", [64, 256])
 def test_llama_128k_other_head_sizes(d):
     """The headline layer's shape and schedule at the two other head sizes."""
-    full_size_case(wl.EXTRA_CONFIGS["llama8b_128k_d%d" % d], 8, heads=[0, 22])
+    full_size_case(wl.EXTRA_CONFIGS["llama8b_128k_d%d" % d], 4, heads=[0, 13, 22, 31])
 
 
 @pytest.mark.parametrize("point", ["d100", "d50", "d20", "d10", "d5"])
 def test_budget_sweep_64k(point):
-    n_rows = {"d100": 2, "d50": 4, "d20": 10, "d10": 16, "d5": 16}[point]
-    full_size_case(wl.SWEEP_64K[point], n_rows, heads=[0, 13, 27])
+    n_rows = {"d100": 5, "d50": 5, "d20": 5, "d10": 9, "d5": 9}[point]   # 28 heads x (7 fixed + these) rows
+    full_size_case(wl.SWEEP_64K[point], n_rows)
 
 
 def test_budget_sweep_64k_uniform_control():
@@ -109,11 +125,11 @@ def test_budget_sweep_64k_uniform_control():
     say("uniform control: k_uni", w.k_start_blocks, "blocks", uni_total, "vs decay", decay_total)
     assert abs(uni_total - decay_total) <= 512
     assert w.k_start_blocks[0] / wl.SWEEP_64K["d10"].k_start_blocks[0] == pytest.approx(0.85, abs=0.05)
-    full_size_case(wl.with_budget(w, w.k_start_blocks, 1.0, ""), 12, heads=[3, 20])
+    full_size_case(wl.with_budget(w, w.k_start_blocks, 1.0, ""), 3)
 
 
 def test_packed_varlen_128k():
-    full_size_case(wl.PACKED_128K, 16, heads=[2, 17, 28])
+    full_size_case(wl.PACKED_128K, 4)                        # 32 heads x (4 sequences x 7 + 4) rows
 
 
 def test_fused_estimate_select_128k_and_most_blocks():
@@ -152,4 +168,4 @@ def test_most_blocks_per_sequence_b64_ragged():
     w = wl.small("max_blocks_b64", seed=51, num_q_heads=2, num_kv_heads=1, seq_lens=(4096 * 64 - 17,),
                  block_size=64, k_start=(40,), n_sink=2, n_local=2, outliers=(32,))
     assert so.total_rows(w.cu_seqlens, w.block_size) == (4096, 4096)
-    full_size_case(w, 10, heads=[0, 1])
+    full_size_case(w, 10)

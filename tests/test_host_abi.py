@@ -148,6 +148,10 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert L.stem_select(good.ref(), 0x1000, 0x1000, 1, 1, 0, 0x1000, None, 8, None) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_select(good.ref(), 0x1000, 0x1000, -1, 1, 0, 0x1000, 0x1000, 8, None) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_select(good.ref(), 0x1000, 0x1000, 3, 3, 0, 0x1000, 0x1000, 4, None) == sb.STEM_ERR_INVALID_ARG
+    # the diagonal is always kept: a local window of zero blocks is refused by both selection calls
+    assert L.stem_select(good.ref(), 0x1000, 0x1000, 2, 0, 0, 0x1000, 0x1000, 8, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_estimate_select(good.ref(), 0x1000, 0x1000, 0x1000, 0.2, 1.0, 1, 0x1000, 2, 0, 0x1000, 0x1000, 8,
+                                  None, 0x1000, 1 << 30, None) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_select(good.ref(), 0x1000, 0x1000, 1, 1, 2, 0x1000, 0x1000, 8, None) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_group_scores(good.ref(), 0x1000, 7, 0x1000, None) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_group_scores(good.ref(), None, 0, 0x1000, None) == sb.STEM_ERR_INVALID_ARG

@@ -128,6 +128,76 @@ def test_ragged_tail_pools_valid_tokens_only():
     assert mv[0, 2] == pytest.approx(np.log(np.linalg.norm(v[8:10, 0], axis=1)).max())
 
 
+def brute_route_ragged(q, k, lo, hi, B, S, h, g, i, j):
+    """Token-level statement of the routing term when blocks may be partial: the average over the S
+    anti-diagonal classes a of the mean logit over the valid cells (r, c) of block pair (i, j) with
+    r = a and c = S-1-a (mod S); a class with no valid cell contributes 0.  Also returns the plain
+    mean over all sampled valid cells, which is a different number when the classes are uneven."""
+    per_class, all_cells = [], []
+    for a in range(S):
+        cells = []
+        for r in range(B):
+            for c in range(B):
+                tq, tk = lo + i * B + r, lo + j * B + c
+                if tq < hi and tk < hi and r % S == a and c % S == S - 1 - a:
+                    cells.append(float(np.dot(q[tq, h], k[tk, g])))
+        per_class.append(sum(cells) / len(cells) if cells else 0.0)
+        all_cells += cells
+    return sum(per_class) / S, (sum(all_cells) / len(all_cells) if all_cells else None)
+
+
+@pytest.mark.parametrize("S", [2, 4, 8])
+def test_strided_routing_term_on_partial_blocks(S):
+    # The reading taken for ad_stride > 1 on a partial last block: Algorithm 1 pools first and
+    # multiplies afterwards, so each residue class is normalised by its own number of valid tokens
+    # when it is pooled; the score is the mean over classes of the class-mean logits (an empty class
+    # counts as 0), NOT the mean over all sampled valid cells.  On full blocks the two coincide.
+    # catches: dividing a class by B/S instead of its valid count, dropping the 1/S, pairing a with a,
+    # skipping empty classes in the average, pooling padding rows
+    B, Hq, Hkv, d = 8, 2, 1, 6
+    cu = [0, 19, 33]            # tails of 3 tokens (classes 3.. empty for S >= 4) and of 6 tokens (uneven classes)
+    q, k, v = rng_qkv(17, 33, Hq, Hkv, d)
+    qb, kb, mv = so.pool_blocks(q, k, v, cu, B, ad_stride=S)
+    sc = so.oam_scores(qb, kb, mv, cu, B, beta=0.0, route_scale=1.0)
+    differs = 0
+    row0 = 0
+    for s_ in range(2):
+        lo, hi = cu[s_], cu[s_ + 1]
+        nb = -(-(hi - lo) // B)
+        for i in range(nb):
+            for j in range(i + 1):
+                for h in range(Hq):
+                    want, cell_mean = brute_route_ragged(q, k, lo, hi, B, S, h, 0, i, j)
+                    assert sc[h, row0 + i, j] == pytest.approx(want, rel=1e-12, abs=1e-12)
+                    if i < nb - 1:          # both blocks full: the reading is the mean over the sampled cells
+                        assert want == pytest.approx(cell_mean, rel=1e-12, abs=1e-12)
+                    elif cell_mean is None:   # no sampled cell is valid: the routing term is 0
+                        assert want == 0.0
+                    elif abs(want - cell_mean) > 1e-6:
+                        differs += 1
+        row0 += nb
+    assert differs > 0          # on the partial blocks it is a reading, not an identity
+    # a class without valid tokens is pooled to zeros
+    if S >= 4:
+        assert not qb[:, 2, 3:].any() and not kb[:, 2, 3:].any()
+
+
+def test_empty_list_gives_empty_sums():
+    # a row without any listed block (the selection never emits one; caller-made lists may):
+    # the sums over an empty key set, out = 0 and lse = log 0 = -inf
+    q, k, v = rng_qkv(19, 12, 2, 1, 4)
+    counts = np.array([[1, 0, 3], [0, 2, 0]], np.int32)
+    idx = np.full((2, 3, 3), -1, np.int32)
+    idx[0, 0, :1] = [0]
+    idx[0, 2, :3] = [0, 1, 2]
+    idx[1, 1, :2] = [0, 1]
+    out, lse = so.sparse_attention(q, k, v, [0, 12], 4, counts, idx, 0.5)
+    for h, r in [(0, 1), (1, 0), (1, 2)]:
+        assert not out[r * 4:(r + 1) * 4, h].any() and np.isneginf(lse[h, r * 4:(r + 1) * 4]).all()
+    for h, r in [(0, 0), (0, 2), (1, 1)]:
+        assert np.isfinite(lse[h, r * 4:(r + 1) * 4]).all()
+
+
 def test_token_level_metric_ranks_like_exact_contribution():
     # Appendix (rank-equivalent scoring): with B = 1, beta = 1, the 1/sqrt(d) routing scale and all
     # ||V_j|| >= 1 (clamp inactive), the top-k of the metric row equals the top-k of the exact
