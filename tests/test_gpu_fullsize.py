@@ -73,13 +73,14 @@ def full_size_case(w, random_rows_per_head, whole_output=False, heads=None):
             t0 = w.cu_seqlens[s]
             assert torch.equal(g_out[t0], data["v"][t0].repeat_interleave(G, dim=0))
     B = w.block_size
+    keys = pu.ListedKeys(qkv, w.cu_seqlens, B, counts, indices, w.softmax_scale)
     if whole_output:
         o_out, o_lse = so.sparse_attention(*qkv, w.cu_seqlens, w.block_size, counts, indices, w.softmax_scale)
         for (lo, hi, nb, row0) in so.sequence_table(w.cu_seqlens, B):
             for h, r in np.argwhere(~same[:, row0:row0 + nb]):
                 o_out[lo + r * B:min(lo + (r + 1) * B, hi), h] = np.nan
                 o_lse[h, lo + r * B:min(lo + (r + 1) * B, hi)] = np.nan
-        max_abs, rel_l2 = pu.check_output(g_out, o_out, w.name, say)
+        max_abs, rel_l2 = pu.check_output(g_out, o_out, w.name, say, keys)
         lse_err = pu.check_lse(g_lse, o_lse, w.name)
         n_pairs = int(same.sum())
     else:
@@ -88,7 +89,8 @@ def full_size_case(w, random_rows_per_head, whole_output=False, heads=None):
         res = pu.oracle_attention_pairs(w, qkv, counts, indices, pairs)
         g = np.concatenate([g_out[t0:t1, h].double().numpy() for h, r, t0, t1, o, l in res])
         o = np.concatenate([o for h, r, t0, t1, o, l in res])
-        max_abs, rel_l2 = pu.check_output_arrays(g, o, w.name, say)
+        where = np.concatenate([np.stack([np.arange(t0, t1), np.full(t1 - t0, h)], axis=1) for h, r, t0, t1, o_, l in res])
+        max_abs, rel_l2 = pu.check_output_arrays(g, o, where, w.name, say, keys)
         gl = np.concatenate([g_lse[h, t0:t1].double().numpy() for h, r, t0, t1, o, l in res])
         ol = np.concatenate([l for h, r, t0, t1, o, l in res])
         lse_err = float(np.abs(gl - ol).max())

@@ -80,7 +80,8 @@ def run_both(w, rows=None, heads=None):
                 if not same[h, row0 + i]:
                     o_out[lo + i * B:min(lo + (i + 1) * B, hi), h] = np.nan
                     o_lse[h, lo + i * B:min(lo + (i + 1) * B, hi)] = np.nan
-    max_abs, rel_l2 = pu.check_output(pf.out, o_out, w.name, say)
+    keys = pu.ListedKeys(qkv, w.cu_seqlens, w.block_size, counts, indices, w.softmax_scale)
+    max_abs, rel_l2 = pu.check_output(pf.out, o_out, w.name, say, keys)
     lse_err = pu.check_lse(pf.lse, o_lse, w.name)
     # out and lse were NaN before the run: every row of every head has been written
     assert not torch.isnan(pf.out).any().item() and not torch.isnan(pf.lse).any().item()
@@ -201,7 +202,7 @@ def test_chunked_prefill_gives_the_rows_of_the_one_piece_call(ad_stride, fused, 
     same = pu.check_lists(w, full.counts.cpu().numpy(), full.indices.cpu().numpy(), counts, indices, scores, say)
     assert same.all()
     o_out, _ = so.sparse_attention(*qkv, cu, B, counts, indices, w.softmax_scale)
-    pu.check_output(out, o_out, w.name)
+    pu.check_output(out, o_out, w.name, say, pu.ListedKeys(qkv, cu, B, counts, indices, w.softmax_scale))
 
 
 @pytest.mark.parametrize("ad_stride", [1, 4])
@@ -264,7 +265,9 @@ def test_group_shared_selection(name, how):
                 if not same[h // G, row0 + i]:
                     o_out[lo + i * B:min(lo + (i + 1) * B, hi), h] = np.nan
                     o_lse[h, lo + i * B:min(lo + (i + 1) * B, hi)] = np.nan
-    pu.check_output(pf.out, o_out, w.name, say)
+    pu.check_output(pf.out, o_out, w.name, say,
+                    pu.ListedKeys(qkv, w.cu_seqlens, B, np.repeat(counts, G, axis=0), np.repeat(indices, G, axis=0),
+                                  w.softmax_scale))
     pu.check_lse(pf.lse, o_lse, w.name)
     # the shared lists differ from the per-head ones (the reduction does something)
     _, c_h, i_h = pu.oracle_select(w, scores)
@@ -295,7 +298,8 @@ def test_zero_blocks_in_the_inputs():
     o_out, _ = so.sparse_attention(*qkv, w.cu_seqlens, w.block_size, counts, indices, w.softmax_scale)
     for h, r in np.argwhere(~same):
         o_out[r * 64:(r + 1) * 64, h] = np.nan
-    pu.check_output(pf.out, o_out, w.name)
+    pu.check_output(pf.out, o_out, w.name, say,
+                    pu.ListedKeys(qkv, w.cu_seqlens, w.block_size, counts, indices, w.softmax_scale))
 
 
 def test_select_is_bit_exact_on_shared_fp32_scores():
@@ -367,7 +371,7 @@ def test_attention_on_given_lists_full_budget_and_random():
                             nbmax, w.softmax_scale, out, lse)
         torch.cuda.synchronize()
         o_out, o_lse = so.sparse_attention(*qkv, cu, B, counts, idx, w.softmax_scale)
-        pu.check_output(out, o_out, mode, say)
+        pu.check_output(out, o_out, mode, say, pu.ListedKeys(qkv, cu, B, counts, idx, w.softmax_scale))
         pu.check_lse(lse, o_lse, mode)
 
 
@@ -426,7 +430,7 @@ def test_rows_without_a_usable_entry_give_zeros_and_minus_infinity(B, d):
                     assert torch.isneginf(lse[h, t0:t1]).all().item(), (kind[(h, row0 + i)], h, i)
                     o_out[t0:t1, h] = np.nan
                     o_lse[h, t0:t1] = np.nan
-    pu.check_output(out, o_out, w.name, say)
+    pu.check_output(out, o_out, w.name, say, pu.ListedKeys(qkv, cu, B, o_counts, o_idx, w.softmax_scale))
     pu.check_lse(lse, o_lse, w.name)
     assert not torch.isnan(out).any().item() and not torch.isnan(lse).any().item()
 
@@ -479,7 +483,7 @@ def test_attention_reference_moves_and_unusable_entries(B, d, sign):
         sb.stem_sparse_attn(shape, qd, kd, vd, torch.from_numpy(c).to(dev), torch.from_numpy(ix).to(dev),
                             ix.shape[2], scale, out, lse)
         torch.cuda.synchronize()
-        max_abs, rel_l2 = pu.check_output(out, o_out, name)
+        max_abs, rel_l2 = pu.check_output(out, o_out, name, say, pu.ListedKeys(qkv, cu, B, clean_c, clean_i, scale))
         if name == "clean":                                           # lse is optional: same output without it
             out2 = torch.full_like(qd, float("nan"))
             sb.stem_sparse_attn(shape, qd, kd, vd, torch.from_numpy(c).to(dev), torch.from_numpy(ix).to(dev),

@@ -86,6 +86,8 @@ def run_with_options(w, seed):
                 if not same[h // rep, row0 + i]:
                     o_out[lo + i * B:min(lo + (i + 1) * B, hi), h] = np.nan
                     o_lse[h, lo + i * B:min(lo + (i + 1) * B, hi)] = np.nan
-    pu.check_output(pf.out, o_out, w.name)
+    pu.check_output(pf.out, o_out, w.name, print,
+                    pu.ListedKeys(qkv, w.cu_seqlens, B, np.repeat(counts, rep, axis=0), np.repeat(indices, rep, axis=0),
+                                  w.softmax_scale))
     if (~np.isnan(o_lse)).any():
         pu.check_lse(pf.lse, o_lse, w.name)
