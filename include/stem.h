@@ -152,6 +152,27 @@ int stem_estimate(const stem_shape* shape, const void* q, const void* k, const v
                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * stem_estimate for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same kernels and same scores as
+ * stem_estimate, but the pooled block representations live in an array inside the library's code
+ * object (STEM_STATIC_WORKSPACE_BYTES per GPU, held from module load until the process ends) instead
+ * of a caller-provided workspace.  The call allocates nothing and frees nothing.
+ *   - STEM_ERR_WORKSPACE if stem_workspace_bytes(shape, ad_stride) exceeds STEM_STATIC_WORKSPACE_BYTES
+ *     (32 MiB: the 128K-token layer with 32/8 heads of size 128 needs 21 MB at ad_stride 1);
+ *     STEM_ERR_UNSUPPORTED for chunked shapes (a chunk's scores need the pooled keys of earlier
+ *     calls, which a shared array cannot promise); STEM_ERR_HIP if the array's address cannot be found.
+ *   - The first call on a device looks the array's device address up (once per device, kept
+ *     afterwards); make that first call outside graph capture.
+ *   - All calls on one GPU share that GPU's array, which keeps the last call's pooled vectors.
+ *     Nothing in it has to start at zero (every call writes all it reads), but two calls that
+ *     overlap in time on one GPU, on different streams or from different threads, race on it.
+ */
+#define STEM_STATIC_WORKSPACE_BYTES (32u << 20)
+int stem_estimate_static(const stem_shape* shape, const void* q, const void* k, const void* v,
+                         float beta, float route_scale, int32_t ad_stride, float* scores,
+                         void* hip_stream);
+
+/*
  * Group-shared selection for grouped-query attention (an extension: the paper derives the method
  * per head).  Reduces the metric over the G = Hq / Hkv query heads of each KV head:
  *   group_scores[g, r, j] = max (STEM_GROUP_MAX) or mean (STEM_GROUP_MEAN) over h in g*G .. g*G+G-1

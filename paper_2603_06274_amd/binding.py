@@ -68,6 +68,7 @@ def lib() -> ctypes.CDLL:
             "stem_pool": [shp, vp, vp, vp, i32, vp, sz, vp],
             "stem_block_scores": [shp, vp, sz, i32, f32, f32, vp, vp],
             "stem_estimate": [shp, vp, vp, vp, f32, f32, i32, vp, vp, sz, vp],
+            "stem_estimate_static": [shp, vp, vp, vp, f32, f32, i32, vp, vp],
             "stem_group_scores": [shp, vp, i32, vp, vp],
             "stem_estimate_select": [shp, vp, vp, vp, f32, f32, i32, vp, i32, i32, vp, vp, i32, vp, vp, sz, vp],
             "stem_select": [shp, vp, vp, i32, i32, i32, vp, vp, i32, vp],
@@ -84,7 +85,7 @@ def lib() -> ctypes.CDLL:
 EXPORTED = ["stem_version", "stem_strerror", "stem_rows", "stem_workspace_bytes",
             "stem_workspace_layout", "stem_budget_schedule", "stem_pool", "stem_block_scores",
             "stem_group_scores", "stem_estimate_select",
-            "stem_estimate", "stem_select", "stem_sparse_attn"]
+            "stem_estimate", "stem_estimate_static", "stem_select", "stem_sparse_attn"]
 
 
 def _check(status: int, where: str) -> None:
@@ -193,6 +194,16 @@ def stem_estimate(shape: Shape, q, k, v, beta: float, route_scale: float, ad_str
     _check(lib().stem_estimate(shape.ref(), _ptr(q), _ptr(k), _ptr(v), float(beta), float(route_scale),
                                int(ad_stride), _ptr(scores), _ptr(workspace),
                                workspace.numel() * workspace.element_size(), _stream()), "stem_estimate")
+
+
+STEM_STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def stem_estimate_static(shape: Shape, q, k, v, beta: float, route_scale: float, ad_stride: int,
+                         scores: torch.Tensor) -> None:
+    """stem_estimate on the library's own per-GPU array: no workspace argument, no allocation."""
+    _check(lib().stem_estimate_static(shape.ref(), _ptr(q), _ptr(k), _ptr(v), float(beta), float(route_scale),
+                                      int(ad_stride), _ptr(scores), _stream()), "stem_estimate_static")
 
 
 STEM_GROUP_MAX, STEM_GROUP_MEAN = 0, 1

@@ -16,7 +16,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libstem_hip.so")
 
-SOURCES = ["stem_api.cpp", "stem_pool.hip", "stem_scores.hip", "stem_select.hip", "stem_attn.hip"]
+SOURCES = ["stem_api.cpp", "stem_pool.hip", "stem_scores.hip", "stem_select.hip", "stem_attn.hip", "stem_static.hip"]
 
 # -packed-fp32-ops: keep the compiler from forming v_pk_*_f32 out of plain float code.
 COMMON = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-I" + os.path.join(ROOT, "include"),

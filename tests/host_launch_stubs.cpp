@@ -27,3 +27,9 @@ int launch_sparse_attn(const Problem&, const void*, const void*, const void*, co
 }
 
 }  // namespace stem
+
+// lives in a file of its own with the device array it uses; the host-only build has no device
+extern "C" int stem_estimate_static(const stem_shape*, const void*, const void*, const void*, float, float, int32_t,
+                                    float*, void*) {
+    return STEM_ERR_HIP;
+}
