@@ -27,10 +27,33 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PAPER_H20_128K_DENSE_EQUIV_TFLOPS = 1.409e14 / 0.420 / 1e12   # dense-causal FLOPs of the layer / 420 ms
 
-# HBM-side bytes per sparse-attention launch on the 128K layer, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this script (profiles/sparse_attn_kernel_llama8b_128k.md): FETCH_SIZE
-# 5.715e6 KiB x 2.0 (copy calibration) + WRITE_SIZE 1.049e6 KiB x 1.0.  Only valid for that workload.
-MEASURED_ATTN_TRAFFIC_BYTES = {"llama8b_128k": 12.8e9}
+ATTN_SOURCE = os.path.join(ROOT, "paper_2603_06274_amd", "csrc", "stem_attn.hip")
+
+
+def git_blob_sha1(path):
+    """The hash git gives the file's content (what `git hash-object` prints)."""
+    import hashlib
+    data = open(path, "rb").read()
+    return hashlib.sha1(b"blob %d\0" % len(data) + data).hexdigest()
+
+
+def measured_attention_traffic(workload):
+    """HBM-side bytes per sparse-attention launch as measured with rocprofv3 --pmc FETCH_SIZE and
+    WRITE_SIZE runs of this script.  The figure lives beside the profile summary it comes from
+    (profiles/sparse_attn_kernel_<workload>.md, a line `traffic_bytes_per_launch: <bytes> kernel_blob:
+    <sha1>`), tagged with the git blob hash of the kernel source it was measured on; it is reported
+    only while that hash is still the source's, otherwise null."""
+    import re
+    path = os.path.join(ROOT, "profiles", "sparse_attn_kernel_%s.md" % workload)
+    current = git_blob_sha1(ATTN_SOURCE)
+    info = {"profile": os.path.relpath(path, ROOT), "kernel_blob_now": current, "kernel_blob_measured": None}
+    if not os.path.exists(path):
+        return None, info
+    m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)\s+kernel_blob:\s*([0-9a-f]{40})", open(path).read())
+    if not m:
+        return None, info
+    info["kernel_blob_measured"] = m.group(2)
+    return (float(m.group(1)) if m.group(2) == current else None), info
 
 
 def median(xs):
@@ -50,7 +73,7 @@ def numpy_threads():
     return 1
 
 
-def cpu_baseline(w, data, dense_flops):
+def cpu_baseline(w, data, dense_flops, gpu_counts, gpu_indices):
     """Times the oracle on KV group 0 (stages 1-2 in full, stage 3 on evenly spaced rows) and
     extrapolates to the layer."""
     import numpy as np
@@ -74,9 +97,13 @@ def cpu_baseline(w, data, dense_flops):
     sampled_blocks = int(counts[:, rows].sum())
     group_blocks = int(counts.sum())
     t_layer = w.num_kv_heads * (t12 + t3 * group_blocks / max(sampled_blocks, 1))
+    # rows of this KV group whose GPU list differs from the oracle's (near-ties of the fp32 metric)
+    kk = min(indices.shape[2], gpu_indices.shape[2])
+    differ = ((gpu_indices[:G, :, :kk] != indices[:, :, :kk]).any(axis=2) | (gpu_counts[:G] != counts))
     return {
         "value": round(dense_flops / t_layer / 1e12, 4), "unit": "TFLOP/s (dense-equivalent)",
-        "cores": numpy_threads(), "kind": "oracle",
+        "cores": numpy_threads(), "host_cpu_count": os.cpu_count(), "kind": "oracle",
+        "list_rows_differing_from_oracle": int(differ.sum()), "list_rows_compared": int(differ.size),
         "sample": "KV group 0 (%d of %d query heads): stages 1-2 in full (%.1f s), stage 3 on %d of %d "
                   "query-block rows (%.1f s, %d listed blocks); layer time extrapolated by listed-block "
                   "count to %.0f s" % (G, w.num_q_heads, t12, n_rows, w.total_rows, t3, sampled_blocks, t_layer),
@@ -184,6 +211,11 @@ def main():
     pool_gbs = pool_bytes / (t_pool * 1e-3) / 1e9
 
     value = dense_flops / (ms_per_step * 1e-3) / 1e12
+    traffic, traffic_info = measured_attention_traffic(w.name)
+    # the whole estimation stage against the HBM roofline: what the method itself has to move is Q, K, V
+    # once, the pooled vectors out and back in, and the causal half of the score tensor out
+    est_bytes = pool_bytes + 4.0 * d * (R * Hq + w.total_rows * Hkv) * args.ad_stride + 4.0 * w.admissible_blocks * Hq
+    est_gbs = est_bytes / (t_est * 1e-3) / 1e9
     # The paper's only number for this path: 420 ms per 128K layer with its default schedule on an
     # NVIDIA H20 (Empirical Latency), i.e. 335 dense-equivalent TFLOP/s for these shapes.  It applies
     # to that schedule only and is another machine's figure: context, not a target.
@@ -203,13 +235,18 @@ def main():
         "attention_dense_equiv_tflops": round(dense_flops / (t_attn_avg * 1e-3) / 1e12, 2),
         "roofline": {"kernel": "sparse_attn_kernel", "bound": "mfma", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_ATTN_TRAFFIC_BYTES.get(w.name) if default_options else None},
+                     "traffic": traffic if default_options else None, "traffic_source": traffic_info},
         "estimate_roofline": {"kernel": "pool_kernel", "bound": "hbm", "achieved": round(pool_gbs, 1),
                               "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(pool_gbs / PEAK_HBM_GBS, 4),
                               "algorithmic_bytes": pool_bytes},
+        "estimate_stage_roofline": {"kernels": "pool_kernel + block_scores_kernel" if not args.fused else
+                                    "pool_kernel + score_select_kernel (selection included)",
+                                    "bound": "hbm", "achieved": round(est_gbs, 1), "peak": PEAK_HBM_GBS,
+                                    "unit": "GB/s", "frac": round(est_gbs / PEAK_HBM_GBS, 4),
+                                    "algorithmic_bytes": est_bytes},
     }
     if not args.no_cpu_baseline and default_options:   # the oracle leg times the default path only
-        result["cpu_baseline"] = cpu_baseline(w, data, dense_flops)
+        result["cpu_baseline"] = cpu_baseline(w, data, dense_flops, pf.counts.cpu().numpy(), pf.indices.cpu().numpy())
     print(json.dumps(result), flush=True)
 
 

@@ -25,6 +25,10 @@
 // under the matrix instructions that follow the tile), and the softmax runs without a running
 // maximum: a per-query reference is set
 // on the first block and moved only when a window of probabilities overflows (slow path).
+// The vector unit's issue slots are what the kernel runs short of (every vector instruction taken
+// out of the loop shows in the run time), so whatever can go elsewhere does: the row sums of the
+// probabilities are taken by the matrix pipe (a 4x4x4 product with a matrix of ones), the
+// per-request address arithmetic by the scalar unit (the scalar offset operand of the loads).
 //
 // The kernel is a template over the block size B (64, 128) and the head size D (64, 128, 256).
 //
@@ -40,6 +44,7 @@ namespace stem {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4_t;
@@ -94,7 +99,9 @@ __device__ __forceinline__ void wait_lgkmcnt(int n) {   // n is a constant after
 // sequence's first row in this KV head and its size ends with the sequence's last row, so rows
 // past the end of a partial last block (and past the end of the tensor) are never read and arrive
 // in LDS as zeros (their keys are masked by causality, their values get weight 0).  A block is a
-// byte offset added to the per-lane offset (one vector add per block), a slice one more add.
+// byte offset added to the per-lane offset (one vector add per block); the slice's offset, which
+// is the same for all lanes, travels in the load's scalar offset operand, which the range check
+// of a raw buffer takes into account (offset >= num_records - scalar offset reads as zero).
 template <int NV>
 struct BlockRequest {
     __amdgpu_buffer_rsrc_t rsrc;
@@ -105,7 +112,7 @@ struct BlockRequest {
                                           int slice_lds_step) const {
         // slice0 = LDS address of this wave's slice for u = 0; slice u lies u*NW KiB further on
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_t*)(slice0 + u * slice_lds_step), 16,
-                                                 lane_off[u % NV] + u * slice_step, 0, 0, 0);
+                                                 lane_off[u % NV], u * slice_step, 0, 0);
     }
 };
 
@@ -159,6 +166,7 @@ struct SoftmaxSchedule {
         for (int c = 0; c < kChecks; ++c) {
             const int slot = check_slot(c);
             if (slot < NS || slot % DT) return false;
+            if (pairs_by(slot - 1) % 2) return false;        // the row sums are taken two pairs at a time
             if (lo > 4 * ((slot - NS) / DT)) return false;   // pairs below the window are consumed (4 per step)
             for (int q = lo; q < pairs_by(slot - 1); ++q)
                 if (use_slot(q) < slot) return false;        // pairs of the window are not consumed yet
@@ -330,7 +338,7 @@ __device__ __forceinline__ void sparse_attn_body(
     // dt*32 + 16*((l>>4)&1) + 4*(l&3); the 64-byte group index dt is XORed with (row & 3)
     const int v_row = hi * 8 + ((lane & 15) >> 2);     // key0 and the +4 leave the swizzle term alone
     const uint32_t v_base0 = v_row * kRowBytes + (v_swz(v_row) << 4) + (((lane >> 4) & 1) << 5) + ((lane & 3) << 3);
-    uint32_t k_base = k_base0, v_base = v_base0;
+    const uint32_t k_base = k_base0, v_base = v_base0;
 
     // Operand n of S^T (matrix instruction n: key tile n/KS, 16-wide step n%KS along d; the lane's
     // 16-byte chunk is 2*(n%KS) + hi) and of O^T (matrix instruction n: 16-key step n/DT, d tile n%DT).
@@ -362,34 +370,37 @@ __device__ __forceinline__ void sparse_attn_body(
 
     f32x16_t s_acc[KT];
     uint32_t p_pk[KT][8];                              // bf16 pairs: [tile][16-key step * 4 + pair]
-    float ps[4];                                       // row-sum partials of the current window
-    float off;                                         // reference in exp2 units
+    f32x4_t l_win = {0.f, 0.f, 0.f, 0.f};              // row sum of the current window (four equal copies)
+    float off = 0.f;                                   // reference in exp2 units; changes on the slow path only
 
     // softmax of pair q (tile q/8, accumulators 2*(q%8) and +1): exp2 domain, reference m_ref,
-    // packed to bf16, summed from the rounded values with one v_dot2c_f32_bf16
+    // packed to bf16.  The row sum is taken from the rounded values, two pairs at a time, by the
+    // matrix pipe: in v_mfma_f32_4x4x4_16B_bf16 lane l supplies column l % 4 of block l / 4 of B (four
+    // values along the contraction) and receives that column of the 4 x 4 result, so with A = ones
+    // every lane gets the sum of its own four values, in each of its four result registers.
     auto softmax_pair = [&](int q) {
         const int t = q >> 3, x = (q & 7) * 2;
         const float p0 = __builtin_amdgcn_exp2f(s_acc[t][x] * sl2 - off);
         const float p1 = __builtin_amdgcn_exp2f(s_acc[t][x + 1] * sl2 - off);
         uint32_t pk = pack_bf16(p0, p1);
-        float sum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pk),
-                                                    __builtin_bit_cast(bf16x2_t, 0x3f803f80u), ps[q & 3], false);
-        // An opaque use of the results at this point of the instruction stream: without it the
+        // An opaque use of the result at this point of the instruction stream: without it the
         // compiler gathers the softmax next to the consumer of the results instead of leaving
         // each pair next to "its" matrix instruction.
-        asm volatile("" : "+v"(pk), "+v"(sum));
+        asm volatile("" : "+v"(pk));
         p_pk[t][q & 7] = pk;
-        ps[q & 3] = sum;
+        if (q & 1) {                                   // windows hold an even number of pairs
+            const uint2 four = make_uint2(p_pk[t][(q & 7) - 1], pk);
+            const uint2 ones = make_uint2(0x3f803f80u, 0x3f803f80u);
+            l_win = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(s16x4_t, ones),
+                                                           __builtin_bit_cast(s16x4_t, four), l_win, 0, 0, 0);
+        }
     };
     auto softmax_slot = [&](int slot) {                // one pair per slot at most (two at d = 64)
 #pragma unroll
         for (int q = pairs_by(slot - 1); q < pairs_by(slot); ++q) softmax_pair(q);
     };
-    auto window_sum = [&]() { return (ps[0] + ps[1]) + (ps[2] + ps[3]); };
-    auto clear_sum = [&]() {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) ps[e] = 0.f;
-    };
+    auto window_sum = [&]() { return l_win[0]; };
+    auto clear_sum = [&]() { l_win = f32x4_t{0.f, 0.f, 0.f, 0.f}; };
     // exp2-domain offset of the reference; a query that has seen nothing yet (m_ref = -inf) uses 0,
     // which keeps its masked scores at exp2(-inf) = 0
     auto reference_offset = [&]() { return m_ref == neg_inf ? 0.f : m_ref * sl2; };
@@ -451,9 +462,6 @@ __device__ __forceinline__ void sparse_attn_body(
         const bool masked = (j == i) || !usable(j_cur);
         const int mask_limit = usable(j_cur) ? qrow - 8 * hi + (i - j) : -1;
 
-        // the bases are made opaque once per block so that the swizzled offsets are recomputed
-        // next to their reads instead of being kept in a dozen registers across the loop
-        asm volatile("" : "+v"(k_base), "+v"(v_base));
         STEM_WAIT_VMCNT(0);
         STEM_BARRIER();                                // K(j) is in LDS; V buffer is free
 
@@ -463,7 +471,6 @@ __device__ __forceinline__ void sparse_attn_body(
         for (int n = 0; n < kAhead; ++n) ka[n] = load_k(n);
         const auto v_rq = v_request(j);
         const int j_nxt = __builtin_amdgcn_readlane(list_reg, (it + 1) & 63);   // 0 past the end
-        off = reference_offset();
         clear_sum();
         STEM_SCHED_FENCE();
 #pragma unroll
