@@ -229,7 +229,8 @@ def main():
         "config": {"workload": w.name, "tokens": T, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d, "block": B,
                    "k_start_blocks": list(w.k_start_blocks), "mu": w.mu, "beta": w.beta,
                    "n_sink": w.n_sink, "n_local": w.n_local, "density": round(density, 5),
-                   "listed_blocks": listed, **({} if default_options else options)},
+                   "listed_blocks": listed, "score_tensor": "tiles without a causal pair not written",
+                   **({} if default_options else options)},
         "stages_ms": {"estimate": round(t_est, 4), "select": round(t_sel, 4), "attention": round(t_attn_avg, 4),
                       "pool_kernel": round(t_pool, 4), "scores_kernel": round(t_scores, 4)},
         "attention_dense_equiv_tflops": round(dense_flops / (t_attn_avg * 1e-3) / 1e12, 2),

@@ -138,23 +138,28 @@ int stem_pool(const stem_shape* shape, const void* q, const void* k, const void*
 /*
  * Algorithm 1 step 3a, Eq. 7, from a workspace pooled with the same ad_stride:
  *   scores[h, r, j] = route_scale * route(h, r, j) + beta * max(0, m_v[g, row0(r) + j])
- * for 0 <= j <= i(r); -inf for i(r) < j < NBmax, with route as defined above from q_bar[h, r] and
- * k_bar[g, row0(r) + j].  scores is fp32 [Hq, R, NBmax].
+ * for 0 <= j <= i(r), with route as defined above from q_bar[h, r] and k_bar[g, row0(r) + j].
+ * scores is fp32 [Hq, R, NBmax].
  * route_scale = 1 is Eq. 7 as printed; 1/sqrt(d) gives the scaling of Eq. 6.
+ * fill_non_causal = 1: every entry i(r) < j < NBmax is written as -inf (the whole rectangle is
+ * defined).  fill_non_causal = 0: the kernel works in tiles of 64 rows x 64 key blocks and does not
+ * touch the tiles that hold no causal pair; inside the other tiles j > i(r) still reads -inf, beyond
+ * them the buffer keeps whatever it held.  stem_select never reads an entry with j > i(r), so the
+ * lists are the same either way; at 128K this halves what stage 1 writes (134 -> 67 MB).
  */
 int stem_block_scores(const stem_shape* shape, const void* workspace, size_t workspace_bytes,
-                      int32_t ad_stride, float beta, float route_scale, float* scores,
-                      void* hip_stream);
+                      int32_t ad_stride, float beta, float route_scale, int32_t fill_non_causal,
+                      float* scores, void* hip_stream);
 
 /* Stage 1 = stem_pool followed by stem_block_scores with the same ad_stride. */
 int stem_estimate(const stem_shape* shape, const void* q, const void* k, const void* v,
-                  float beta, float route_scale, int32_t ad_stride, float* scores,
-                  void* workspace, size_t workspace_bytes, void* hip_stream);
+                  float beta, float route_scale, int32_t ad_stride, int32_t fill_non_causal,
+                  float* scores, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
- * stem_estimate for callers that cannot allocate device memory: code under HIP graph capture,
- * tight serving loops, harnesses that forbid hipMalloc.  Same kernels and same scores as
- * stem_estimate, but the pooled block representations live in an array inside the library's code
+ * stem_estimate (with fill_non_causal = 1) for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and
+ * same scores as stem_estimate, but the pooled block representations live in an array inside the library's code
  * object (STEM_STATIC_WORKSPACE_BYTES per GPU, held from module load until the process ends) instead
  * of a caller-provided workspace.  The call allocates nothing and frees nothing.
  *   - STEM_ERR_WORKSPACE if stem_workspace_bytes(shape, ad_stride) exceeds STEM_STATIC_WORKSPACE_BYTES
@@ -176,7 +181,8 @@ int stem_estimate_static(const stem_shape* shape, const void* q, const void* k, 
  * Group-shared selection for grouped-query attention (an extension: the paper derives the method
  * per head).  Reduces the metric over the G = Hq / Hkv query heads of each KV head:
  *   group_scores[g, r, j] = max (STEM_GROUP_MAX) or mean (STEM_GROUP_MEAN) over h in g*G .. g*G+G-1
- *                           of scores[h, r, j]                 (-inf stays -inf)
+ *                           of scores[h, r, j]                 (-inf stays -inf; entries that
+ *                           stem_block_scores left unwritten stay unspecified, and unread)
  * scores is fp32 [Hq, R, NBmax], group_scores fp32 [Hkv, R, NBmax].  Selecting from group_scores
  * with lists_per_kv_head = 1 gives one list per (KV head, row), which stem_sparse_attn then uses
  * for all G heads of the group: G times fewer lists, and the heads of a group read the same K/V

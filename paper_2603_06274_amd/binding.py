@@ -66,8 +66,8 @@ def lib() -> ctypes.CDLL:
             "stem_budget_schedule": [shp, ctypes.POINTER(ctypes.c_double), ctypes.c_double, i32, i32, i32,
                                      ctypes.POINTER(i32), ctypes.POINTER(i32)],
             "stem_pool": [shp, vp, vp, vp, i32, vp, sz, vp],
-            "stem_block_scores": [shp, vp, sz, i32, f32, f32, vp, vp],
-            "stem_estimate": [shp, vp, vp, vp, f32, f32, i32, vp, vp, sz, vp],
+            "stem_block_scores": [shp, vp, sz, i32, f32, f32, i32, vp, vp],
+            "stem_estimate": [shp, vp, vp, vp, f32, f32, i32, i32, vp, vp, sz, vp],
             "stem_estimate_static": [shp, vp, vp, vp, f32, f32, i32, vp, vp],
             "stem_group_scores": [shp, vp, i32, vp, vp],
             "stem_estimate_select": [shp, vp, vp, vp, f32, f32, i32, vp, i32, i32, vp, vp, i32, vp, vp, sz, vp],
@@ -182,17 +182,17 @@ def stem_pool(shape: Shape, q, k, v, ad_stride: int, workspace: torch.Tensor) ->
 
 
 def stem_block_scores(shape: Shape, workspace: torch.Tensor, ad_stride: int, beta: float,
-                      route_scale: float, scores: torch.Tensor) -> None:
+                      route_scale: float, scores: torch.Tensor, fill_non_causal: bool = True) -> None:
     _check(lib().stem_block_scores(shape.ref(), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), int(ad_stride),
-                                   float(beta), float(route_scale), _ptr(scores), _stream()),
-           "stem_block_scores")
+                                   float(beta), float(route_scale), int(bool(fill_non_causal)), _ptr(scores),
+                                   _stream()), "stem_block_scores")
 
 
 def stem_estimate(shape: Shape, q, k, v, beta: float, route_scale: float, ad_stride: int,
-                  scores: torch.Tensor, workspace: torch.Tensor) -> None:
+                  scores: torch.Tensor, workspace: torch.Tensor, fill_non_causal: bool = True) -> None:
     _check(lib().stem_estimate(shape.ref(), _ptr(q), _ptr(k), _ptr(v), float(beta), float(route_scale),
-                               int(ad_stride), _ptr(scores), _ptr(workspace),
+                               int(ad_stride), int(bool(fill_non_causal)), _ptr(scores), _ptr(workspace),
                                workspace.numel() * workspace.element_size(), _stream()), "stem_estimate")
 
 

@@ -214,11 +214,12 @@ int stem_pool(const stem_shape* shape, const void* q, const void* k, const void*
 }
 
 int stem_block_scores(const stem_shape* shape, const void* workspace, size_t workspace_bytes,
-                      int32_t ad_stride, float beta, float route_scale, float* scores,
-                      void* hip_stream) {
+                      int32_t ad_stride, float beta, float route_scale, int32_t fill_non_causal,
+                      float* scores, void* hip_stream) {
     Problem p;
     int st = make_problem(shape, &p);
     if (st != STEM_OK) return st;
+    if (fill_non_causal != 0 && fill_non_causal != 1) return STEM_ERR_INVALID_ARG;
     if ((st = check_ad_stride(p, ad_stride)) != STEM_OK) return st;
     if (!workspace || !aligned16(workspace) || !scores || !aligned16(scores)) return STEM_ERR_INVALID_ARG;
     if (!std::isfinite(beta) || !std::isfinite(route_scale)) return STEM_ERR_INVALID_ARG;
@@ -228,14 +229,15 @@ int stem_block_scores(const stem_shape* shape, const void* workspace, size_t wor
     const char* ws = static_cast<const char*>(workspace);
     return launch_block_scores(p, ad_stride, reinterpret_cast<const float*>(ws + w.q_bar),
                                reinterpret_cast<const float*>(ws + w.k_bar),
-                               reinterpret_cast<const float*>(ws + w.m_v), beta, route_scale, scores,
-                               static_cast<hipStream_t>(hip_stream));
+                               reinterpret_cast<const float*>(ws + w.m_v), beta, route_scale,
+                               fill_non_causal != 0, scores, static_cast<hipStream_t>(hip_stream));
 }
 
 int stem_estimate(const stem_shape* shape, const void* q, const void* k, const void* v, float beta,
-                  float route_scale, int32_t ad_stride, float* scores, void* workspace,
-                  size_t workspace_bytes, void* hip_stream) {
+                  float route_scale, int32_t ad_stride, int32_t fill_non_causal, float* scores,
+                  void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!scores || !aligned16(scores)) return STEM_ERR_INVALID_ARG;
+    if (fill_non_causal != 0 && fill_non_causal != 1) return STEM_ERR_INVALID_ARG;
     if (!std::isfinite(beta) || !std::isfinite(route_scale)) return STEM_ERR_INVALID_ARG;
     Problem p;
     int st = make_problem(shape, &p);
@@ -243,8 +245,8 @@ int stem_estimate(const stem_shape* shape, const void* q, const void* k, const v
     if ((st = check_ad_stride(p, ad_stride)) != STEM_OK) return st;
     st = stem_pool(shape, q, k, v, ad_stride, workspace, workspace_bytes, hip_stream);
     if (st != STEM_OK) return st;
-    return stem_block_scores(shape, workspace, workspace_bytes, ad_stride, beta, route_scale, scores,
-                             hip_stream);
+    return stem_block_scores(shape, workspace, workspace_bytes, ad_stride, beta, route_scale,
+                             fill_non_causal, scores, hip_stream);
 }
 
 int stem_estimate_select(const stem_shape* shape, const void* q, const void* k, const void* v,

@@ -46,8 +46,8 @@ int check_ad_stride(const Problem& p, int ad_stride);
 int launch_pool(const Problem& p, int ad_stride, const void* q, const void* k, const void* v,
                 float* q_bar, float* k_bar, float* m_v, hipStream_t stream);
 int launch_block_scores(const Problem& p, int ad_stride, const float* q_bar, const float* k_bar,
-                        const float* m_v, float beta, float route_scale, float* scores,
-                        hipStream_t stream);
+                        const float* m_v, float beta, float route_scale, bool fill_non_causal,
+                        float* scores, hipStream_t stream);
 int launch_group_scores(const Problem& p, const float* scores, int reduce, float* group_scores,
                         hipStream_t stream);
 // heads = number of lists per row: Hq, or Hkv for group-shared lists

@@ -12,7 +12,8 @@
 // one 16-byte read and feeds them to four products.  Which depth position a product step pairs is
 // free as long as both operands agree, so step (u, x) takes position 8u + x from the lower half
 // of the wave and 8u + 4 + x from the upper half.  The loads of the next slice are in flight
-// during the products of the current one.  Tiles above the diagonal are only filled with -inf.
+// during the products of the current one.  Tiles above the diagonal are only filled with -inf, or
+// left alone if the caller does not want the rectangle completed (the selection never reads them).
 #include "stem_common.h"
 
 namespace stem {
@@ -28,7 +29,7 @@ struct TileTable {
 __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
     const float* __restrict__ q_bar, const float* __restrict__ k_bar, const float* __restrict__ m_v,
     float* __restrict__ scores, SeqTable seq, TileTable tiles, int R, int Rk, int NBmax, int G, int S,
-    int d_log2, float beta, float route_scale) {
+    int d_log2, float beta, float route_scale, bool fill_non_causal) {
     // sequence and local row tile of this workgroup
     int s = 0;
     for (int x = 1; x < seq.batch; ++x) s = ((int)blockIdx.x >= tiles.tile_start[x]) ? x : s;
@@ -48,14 +49,19 @@ __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
     const float neg_inf = -__builtin_huge_valf();
 
     if (j0 > first + i0 + kTile - 1) {                 // entirely above the diagonal
+        if (!fill_non_causal) return;
+        const bool vec = (NBmax & 3) == 0;             // rows 16-byte aligned (the base is)
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
-            const int i = i0 + ti * 4 + x;
+            const int i = i0 + x * 16 + ti;            // a wave stores four rows of 256 contiguous bytes
             if (i >= n_rows) continue;
+            const int j = j0 + tj * 4;
+            if (vec && j + 3 < NBmax) {
+                *reinterpret_cast<float4*>(out + (int64_t)i * NBmax + j) = make_float4(neg_inf, neg_inf, neg_inf, neg_inf);
+            } else {
 #pragma unroll
-            for (int y = 0; y < 4; ++y) {
-                const int j = j0 + tj * 4 + y;
-                if (j < NBmax) out[(int64_t)i * NBmax + j] = neg_inf;
+                for (int y = 0; y < 4; ++y)
+                    if (j + y < NBmax) out[(int64_t)i * NBmax + j + y] = neg_inf;
             }
         }
         return;
@@ -137,8 +143,8 @@ __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
 }
 
 int launch_block_scores(const Problem& p, int ad_stride, const float* q_bar, const float* k_bar,
-                        const float* m_v, float beta, float route_scale, float* scores,
-                        hipStream_t stream) {
+                        const float* m_v, float beta, float route_scale, bool fill_non_causal,
+                        float* scores, hipStream_t stream) {
     TileTable tiles;
     int total = 0;
     for (int s = 0; s <= STEM_MAX_BATCH; ++s) {
@@ -149,7 +155,8 @@ int launch_block_scores(const Problem& p, int ad_stride, const float* q_bar, con
     if (p.Hq > 65535) return STEM_ERR_UNSUPPORTED;
     dim3 grid(total, (p.NBmax + kTile - 1) / kTile, p.Hq), block(kScoreThreads);
     hipLaunchKernelGGL(block_scores_kernel, grid, block, 0, stream, q_bar, k_bar, m_v, scores, p.seq,
-                       tiles, p.R, p.Rk, p.NBmax, p.G, ad_stride, __builtin_ctz(p.d), beta, route_scale);
+                       tiles, p.R, p.Rk, p.NBmax, p.G, ad_stride, __builtin_ctz(p.d), beta, route_scale,
+                       fill_non_causal);
     return check_launch();
 }
 

@@ -37,11 +37,15 @@ __device__ __forceinline__ void select_row(Load load, int i, int row_budget, int
     k = min(k, min(i + 1, kmax));
     const int need = max(0, k - forced);               // free blocks to pick, <= nfree
 
+    // groups of 64 candidates beyond the row's free range hold nothing: every loop over the items
+    // skips them (a wave-uniform test), so a short row costs what it holds, not ITEMS
+    const int items = (nfree + 63) >> 6;
     uint32_t key[ITEMS];
 #pragma unroll
     for (int e = 0; e < ITEMS; ++e) {
         const int j = fs + e * 64 + lane;
-        key[e] = (j < fe) ? ordered_key(load(j)) : 0u; // 0 sorts below every real key
+        key[e] = 0u;                                   // 0 sorts below every real key
+        if (e < items && j < fe) key[e] = ordered_key(load(j));
     }
 
     uint32_t tau = 0;
@@ -52,7 +56,8 @@ __device__ __forceinline__ void select_row(Load load, int i, int row_budget, int
             const uint32_t cand = tau | (1u << bit);
             int cnt = 0;
 #pragma unroll
-            for (int e = 0; e < ITEMS; ++e) cnt += __popcll(__ballot(key[e] >= cand));
+            for (int e = 0; e < ITEMS; ++e)
+                if (e < items) cnt += __popcll(__ballot(key[e] >= cand));
             if (cnt >= need) tau = cand;
             exact = cnt == need;
         }
@@ -63,7 +68,8 @@ __device__ __forceinline__ void select_row(Load load, int i, int row_budget, int
         } else {
             int above = 0;
 #pragma unroll
-            for (int e = 0; e < ITEMS; ++e) above += __popcll(__ballot(key[e] > tau));
+            for (int e = 0; e < ITEMS; ++e)
+                if (e < items) above += __popcll(__ballot(key[e] > tau));
             n_eq = need - above;
         }
     }
@@ -76,16 +82,18 @@ __device__ __forceinline__ void select_row(Load load, int i, int row_budget, int
         int eq_seen = 0;
 #pragma unroll
         for (int e = 0; e < ITEMS; ++e) {
-            const int j = fs + e * 64 + lane;
-            const bool valid = j < fe;
-            const bool eq = valid && !take_all && key[e] == tau;
-            const uint64_t eq_mask = __ballot(eq);
-            const bool take = valid && (take_all || key[e] > tau ||
-                                        (eq && eq_seen + lanes_below(eq_mask, lane) < n_eq));
-            const uint64_t take_mask = __ballot(take);
-            if (take) out[base + lanes_below(take_mask, lane)] = j;
-            base += __popcll(take_mask);
-            eq_seen += __popcll(eq_mask);
+            if (e < items) {
+                const int j = fs + e * 64 + lane;
+                const bool valid = j < fe;
+                const bool eq = valid && !take_all && key[e] == tau;
+                const uint64_t eq_mask = __ballot(eq);
+                const bool take = valid && (take_all || key[e] > tau ||
+                                            (eq && eq_seen + lanes_below(eq_mask, lane) < n_eq));
+                const uint64_t take_mask = __ballot(take);
+                if (take) out[base + lanes_below(take_mask, lane)] = j;
+                base += __popcll(take_mask);
+                eq_seen += __popcll(eq_mask);
+            }
         }
     }
     const int tail = min(i + 1 - fe, k - base);        // forced tail always fits: k >= forced

@@ -46,6 +46,6 @@ extern "C" int stem_estimate_static(const stem_shape* shape, const void* q, cons
     if (need > (size_t)STEM_STATIC_WORKSPACE_BYTES) return STEM_ERR_WORKSPACE;
     void* ws = device_scratch();
     if (ws == nullptr) return STEM_ERR_HIP;
-    return stem_estimate(shape, q, k, v, beta, route_scale, ad_stride, scores, ws,
+    return stem_estimate(shape, q, k, v, beta, route_scale, ad_stride, 1, scores, ws,
                          (size_t)STEM_STATIC_WORKSPACE_BYTES, hip_stream);
 }

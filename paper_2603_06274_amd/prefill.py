@@ -22,7 +22,8 @@ class StemPrefill:
                  block_size: int, k_start_blocks: Sequence[float], mu: float = 0.7, k_min: int = 0,
                  n_sink: int = 4, n_local: int = 4, beta: float = 0.2, route_scale: float = 1.0,
                  softmax_scale: Optional[float] = None, want_lse: bool = False, ad_stride: int = 1,
-                 chunk=None, workspace: Optional[torch.Tensor] = None, group_share: Optional[str] = None):
+                 chunk=None, workspace: Optional[torch.Tensor] = None, group_share: Optional[str] = None,
+                 fill_scores: bool = False):
         if not (q.is_cuda and k.is_cuda and v.is_cuda):
             raise RuntimeError("StemPrefill needs device tensors; there is no CPU path")
         assert q.dtype == k.dtype == v.dtype == torch.bfloat16
@@ -32,6 +33,9 @@ class StemPrefill:
         self.n_sink, self.n_local = int(n_sink), int(n_local)
         self.beta, self.route_scale = float(beta), float(route_scale)
         self.ad_stride = int(ad_stride)
+        # False: the score kernel skips the tiles that hold no causal pair (the selection never reads
+        # them); True: the whole [Hq, R, NBmax] rectangle is defined, -inf above the diagonal
+        self.fill_scores = bool(fill_scores)
         # group_share "max" / "mean": one list per (KV head, row) from the group-reduced metric
         assert group_share in (None, "max", "mean")
         self.group_share = group_share
@@ -58,14 +62,14 @@ class StemPrefill:
 
     def estimate(self) -> None:
         sb.stem_estimate(self.shape, self.q, self.k, self.v, self.beta, self.route_scale,
-                         self.ad_stride, self.scores, self.workspace)
+                         self.ad_stride, self.scores, self.workspace, self.fill_scores)
 
     def pool(self) -> None:
         sb.stem_pool(self.shape, self.q, self.k, self.v, self.ad_stride, self.workspace)
 
     def block_scores(self) -> None:
         sb.stem_block_scores(self.shape, self.workspace, self.ad_stride, self.beta, self.route_scale,
-                             self.scores)
+                             self.scores, self.fill_scores)
 
     def select(self) -> None:
         if self.group_share:

@@ -8,7 +8,7 @@ namespace stem {
 int launch_pool(const Problem&, int, const void*, const void*, const void*, float*, float*, float*, hipStream_t) {
     return STEM_OK;
 }
-int launch_block_scores(const Problem&, int, const float*, const float*, const float*, float, float, float*,
+int launch_block_scores(const Problem&, int, const float*, const float*, const float*, float, float, bool, float*,
                         hipStream_t) {
     return STEM_OK;
 }

@@ -41,7 +41,7 @@ def device_prefill(w: wl.Workload, data, want_lse=True, ad_stride=1) -> StemPref
     q, k, v = (data[x].to(dev) for x in "qkv")
     return StemPrefill(q, k, v, w.cu_seqlens, w.block_size, w.k_start_blocks, w.mu, w.k_min, w.n_sink,
                        w.n_local, w.beta, w.route_scale, w.softmax_scale, want_lse=want_lse,
-                       ad_stride=ad_stride)
+                       ad_stride=ad_stride, fill_scores=True)
 
 
 def oracle_estimate(w: wl.Workload, qkv, ad_stride=1):

@@ -168,7 +168,7 @@ def test_chunked_prefill_gives_the_rows_of_the_one_piece_call(ad_stride, fused, 
         qc = torch.cat([q[cu[s] + starts[s]:cu[s] + ends[s]] for s in range(2)]).contiguous()
         pf = StemPrefill(qc, k, v, cu, B, w.k_start_blocks, w.mu, w.k_min, w.n_sink, w.n_local, w.beta,
                          w.route_scale, w.softmax_scale, want_lse=True, chunk=(starts, ends), workspace=ws,
-                         ad_stride=ad_stride)
+                         ad_stride=ad_stride, fill_scores=True)
         if fused:
             chunk_dump = torch.empty_like(pf.scores)
             pf.estimate_select(chunk_dump)
@@ -246,7 +246,8 @@ def test_group_shared_selection(name, how):
     dev = torch.device("cuda:0")
     q, k, v = (data[x].to(dev) for x in "qkv")
     pf = StemPrefill(q, k, v, w.cu_seqlens, w.block_size, w.k_start_blocks, w.mu, w.k_min, w.n_sink,
-                     w.n_local, w.beta, w.route_scale, w.softmax_scale, want_lse=True, group_share=how)
+                     w.n_local, w.beta, w.route_scale, w.softmax_scale, want_lse=True, group_share=how,
+                     fill_scores=True)
     pf.run()
     torch.cuda.synchronize()
     scores = pu.oracle_estimate(w, qkv)[3]
@@ -300,6 +301,41 @@ def test_zero_blocks_in_the_inputs():
         o_out[r * 64:(r + 1) * 64, h] = np.nan
     pu.check_output(pf.out, o_out, w.name, say,
                     pu.ListedKeys(qkv, w.cu_seqlens, w.block_size, counts, indices, w.softmax_scale))
+
+
+@pytest.mark.parametrize("name", ["long_b128", "packed_b128", "kv8_b128"])
+def test_scores_without_the_non_causal_fill(name):
+    """fill_non_causal = 0: tiles (64 rows x 64 key blocks) without a causal pair are not touched, the
+    others are written exactly as with the fill, and the selection and the output do not change."""
+    w = SMALL[name] if name != "long_b128" else wl.small("long_b128", seed=23, num_q_heads=2, num_kv_heads=2,
+                                                          seq_lens=(20000,), block_size=128, k_start=(12,),
+                                                          n_sink=2, n_local=2, outliers=(6,))
+    data = wl.generate(w)
+    full = pu.device_prefill(w, data)                  # fill_scores = True
+    full.run()
+    lean = pu.device_prefill(w, data)
+    lean.fill_scores = False
+    lean.scores.fill_(float("nan"))
+    lean.run()
+    torch.cuda.synchronize()
+    a, b = full.scores.cpu().numpy(), lean.scores.cpu().numpy()
+    touched = ~np.isnan(b)
+    assert np.array_equal(a[touched].view(np.int32), b[touched].view(np.int32))     # bit-identical where written
+    causal = np.isfinite(a)
+    assert touched[causal].all()                       # every causal entry is written
+    untouched = int((~touched).sum())
+    R, nbmax = full.rows, full.nbmax
+    say("%s: %d of %d score entries left untouched" % (w.name, untouched, a.size))
+    if max(w.blocks_per_seq) > 128:
+        assert untouched > a.size // 8                 # whole tiles above the diagonal were skipped
+    # an untouched entry lies in a 64 x 64 tile that holds no causal pair
+    for (lo, hi, nb, row0) in so.sequence_table(w.cu_seqlens, w.block_size):
+        for i in range(nb):
+            first_skipped = 64 * (i // 64) + 64        # first key block of the first tile above the row's tile row
+            assert touched[:, row0 + i, :min(first_skipped, nbmax)].all()
+            assert not touched[:, row0 + i, first_skipped:].any()
+    assert torch.equal(full.counts, lean.counts) and torch.equal(full.indices, lean.indices)
+    assert torch.equal(full.out, lean.out) and torch.equal(full.lse, lean.lse)
 
 
 def test_select_is_bit_exact_on_shared_fp32_scores():

@@ -142,9 +142,11 @@ def test_bad_arguments_are_rejected_on_the_host():
     # a workspace sized for block means is too small for four partial means per block
     small_ws = sb.stem_workspace_bytes(good, 1)
     assert L.stem_pool(good.ref(), 0x1000, 0x1000, 0x1000, 4, 0x1000, small_ws, None) == sb.STEM_ERR_WORKSPACE
-    assert L.stem_estimate(good.ref(), 0x1000, 0x1000, 0x1000, 0.2, 1.0, 32, 0x1000, 0x1000, 1 << 30, None) == sb.STEM_ERR_UNSUPPORTED
-    assert L.stem_estimate(good.ref(), 0x1000, 0x1000, 0x1000, 0.2, 1.0, 0, 0x1000, 0x1000, 1 << 30, None) == sb.STEM_ERR_INVALID_ARG
-    assert L.stem_block_scores(good.ref(), 0x1000, 1 << 30, 1, float("nan"), 1.0, 0x1000, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_estimate(good.ref(), 0x1000, 0x1000, 0x1000, 0.2, 1.0, 32, 1, 0x1000, 0x1000, 1 << 30, None) == sb.STEM_ERR_UNSUPPORTED
+    assert L.stem_estimate(good.ref(), 0x1000, 0x1000, 0x1000, 0.2, 1.0, 0, 1, 0x1000, 0x1000, 1 << 30, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_estimate(good.ref(), 0x1000, 0x1000, 0x1000, 0.2, 1.0, 1, 2, 0x1000, 0x1000, 1 << 30, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_block_scores(good.ref(), 0x1000, 1 << 30, 1, float("nan"), 1.0, 1, 0x1000, None) == sb.STEM_ERR_INVALID_ARG
+    assert L.stem_block_scores(good.ref(), 0x1000, 1 << 30, 1, 0.2, 1.0, -1, 0x1000, None) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_select(good.ref(), 0x1000, 0x1000, 1, 1, 0, 0x1000, None, 8, None) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_select(good.ref(), 0x1000, 0x1000, -1, 1, 0, 0x1000, 0x1000, 8, None) == sb.STEM_ERR_INVALID_ARG
     assert L.stem_select(good.ref(), 0x1000, 0x1000, 3, 3, 0, 0x1000, 0x1000, 4, None) == sb.STEM_ERR_INVALID_ARG
