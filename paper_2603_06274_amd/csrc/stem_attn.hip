@@ -38,6 +38,8 @@
 // 4-row x 32-byte footprint of a transposing read.  At D = 64 two 128-byte rows share the 64
 // banks, so the terms are ((row >> 1) & 7) and ((row >> 1) & 1) there.  The swizzle is applied on
 // the global side (each lane fetches the chunk that belongs at its LDS position).
+#include <type_traits>
+
 #include "stem_common.h"
 
 namespace stem {
@@ -431,6 +433,28 @@ __device__ __forceinline__ void sparse_attn_body(
 #pragma unroll
         for (int q = q_lo; q < q_hi; ++q) softmax_pair(q);
     };
+    // The first window of a row, pairs [0, q_hi): O and l are still zero, so there is nothing to
+    // rescale; a query that sees none of the window's keys keeps m_ref = -inf (offset 0, zero
+    // probabilities) and gets its reference from a later window's slow path.
+    auto first_window = [&](int q_hi) {
+        float mx4[4] = {neg_inf, neg_inf, neg_inf, neg_inf};
+#pragma unroll
+        for (int q = 0; q < q_hi; ++q) {
+            mx4[q & 3] = fmaxf(mx4[q & 3], fmaxf(s_acc[q >> 3][(q & 7) * 2], s_acc[q >> 3][(q & 7) * 2 + 1]));
+        }
+        float mx = fmaxf(fmaxf(mx4[0], mx4[1]), fmaxf(mx4[2], mx4[3]));
+        {
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+            mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));   // both lanes of the query
+        }
+        m_ref = mx;
+        off = reference_offset();
+        clear_sum();
+#pragma unroll
+        for (int q = 0; q < q_hi; ++q) softmax_pair(q);
+        l_run += window_sum();
+        clear_sum();
+    };
     // A window needs the slow path if a query has no reference yet (nothing visible to it so far:
     // every query on the first block) or if its sum is not a modest finite number (a probability
     // above 2^16, inf, NaN: the reference is too low for this window).
@@ -454,7 +478,11 @@ __device__ __forceinline__ void sparse_attn_body(
     constexpr int kStepsPerRequestK = NS / KS;         // the next K's under all of O^T
     const f32x16_t zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    for (int it = 0; it < cnt; ++it) {
+    // One listed block.  The first block of a row is a version of its own (first_tag = true): no
+    // query has a reference yet, so the probabilities of the first window cannot be formed under
+    // the S^T products; they are formed once, at the first check point, from the window's maximum.
+    auto one_block = [&](int it, auto first_tag) {
+        constexpr bool kFirst = decltype(first_tag)::value;
         const int j = clamped(j_cur);
         const bool has_next = it + 1 < cnt;
         if (((it + 1) & 63) == 0) list_reg = list_chunk(it + 1);
@@ -486,7 +514,7 @@ __device__ __forceinline__ void sparse_attn_body(
                     v_rq.issue(n / kStepsPerRequestV, v_slice0, slice_step, slice_lds_step);
                 s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[n % kSlots]), q_reg[n % KS],
                                                                   (n % KS) == 0 ? zero16 : s_acc[t], 0, 0, 0);
-                softmax_slot(n);
+                if constexpr (!kFirst) softmax_slot(n);
                 STEM_SCHED_FENCE();
             }
             if (masked) mask_tile(t, mask_limit);
@@ -520,12 +548,15 @@ __device__ __forceinline__ void sparse_attn_body(
                 STEM_SCHED_FENCE();
             }
         };
-        check_window(0);
+        if constexpr (kFirst) first_window(pairs_by(kCheckSlot[0] - 1));
+        else check_window(0);
         pv_range(0, kCheckSlot[1] - NS);
         check_window(1);
         pv_range(kCheckSlot[1] - NS, NS);
         j_cur = j_nxt;
-    }
+    };
+    if (cnt > 0) one_block(0, std::true_type{});
+    for (int it = 1; it < cnt; ++it) one_block(it, std::false_type{});
     STEM_WAIT_VMCNT(0);                                // no request may outlive the workgroup's LDS
 
     // ---- normalise and store: accumulator x of d tile dt is column dt*32 + 8*(x/4) + 4*hi + x%4 ----
