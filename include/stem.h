@@ -36,6 +36,10 @@
  *     sequence for the schedule, the causal limit and the windows, so the chunks of a prompt give
  *     the rows of the one-piece call.  chunk_start must be a multiple of B, chunk_end a multiple
  *     of B or the sequence's length; an empty chunk (start == end) contributes nothing.
+ *   - Q, K and V are expected to hold finite values.  An inf or NaN in them is not detected: it
+ *     spreads as IEEE arithmetic spreads it (a non-finite key or value makes the output rows that
+ *     attend to it non-finite, a non-finite pooled score is ranked by its bit pattern), and
+ *     affects nothing else; no entry point reads or writes out of bounds or hangs because of it.
  *   - Supported: head_dim 64, 128 or 256; block_size 64 or 128; 1 <= batch <= STEM_MAX_BATCH; Hq a
  *     multiple of Hkv; at most STEM_MAX_BLOCKS blocks per sequence.
  */
@@ -87,8 +91,13 @@ int stem_rows(const stem_shape* shape, int32_t* host_total_rows, int32_t* host_m
  * ad_stride S, taken by the stage-1 entry points: the stride of the anti-diagonal sample that the
  * pooled routing term stands for (Algorithm 1 steps 1 and 3a).  A block keeps S partial means,
  * one per residue class of the in-block token position modulo S, and the routing term of a block
- * pair is the mean over the positions (r, c) with (r + c) mod S = S - 1 of <Q_r, K_c>:
- *     route = (1 / S) * sum over a < S of <q_bar[.., a, :], k_bar[.., S - 1 - a, :]>.
+ * pair is
+ *     route = (1 / S) * sum over a < S of <q_bar[.., a, :], k_bar[.., S - 1 - a, :]>,
+ * the mean over the S anti-diagonal classes of the class's mean logit <Q_r, K_c> (r in class a, c in
+ * class S - 1 - a).  On full blocks that is the mean of <Q_r, K_c> over all positions with
+ * (r + c) mod S = S - 1; on a partial last block each class is normalised by its own number of
+ * valid tokens (pooling comes first, the product second, as in Algorithm 1) and a class without
+ * valid tokens contributes 0.
  * S = 1 is block-mean pooling (one vector per block, the 2 N^2 d / B^2 metric cost of the
  * Complexity Analysis); larger S samples the block's logits more finely at S times the cost.
  * Supported: S in {1, 2, 4, 8, 16}; other divisors of B return STEM_ERR_UNSUPPORTED, values that
@@ -231,12 +240,17 @@ int stem_estimate_select(const stem_shape* shape, const void* q, const void* k, 
  * over the tokens u <= t of the key blocks indices[h, r, 0 .. counts[h,r]) (of indices[h / G, r, ..]
  * with counts [Hkv, R] and indices [Hkv, R, kmax] if lists_per_kv_head = 1).  bf16 inputs, bf16 MFMA
  * products with fp32 accumulation, fp32 softmax, bf16 output with Q's strides.  softmax_scale > 0.
- * lse (device fp32 [Hq, T], may be NULL) receives log sum_u exp(softmax_scale * <Q,K>) per query.
+ * lse (device fp32 [Hq, T], may be NULL) receives log sum_u exp(softmax_scale * <Q,K>) per query,
+ * accurate to 4e-3 absolute: the softmax runs in fp32, but the row sum is taken over the
+ * probabilities as the second matrix product uses them, rounded to bf16 (each within 2^-8 of its
+ * fp32 value), which makes every output row an exact convex combination of value rows; a caller
+ * that merges partial results through lse inherits that bound.  A query with no visible key gets
+ * lse = -inf.
  * Any list is accepted, not only stem_select's, provided each row's list is ascending, causal
  * (entries <= i) and holds the diagonal block i.  Lists are not validated: entries outside 0..i
  * contribute nothing (they cost the time of a block, never an out-of-bounds access); a row with
- * no usable entry yields zeros.  STEM_ERR_UNSUPPORTED if one sequence of one KV head spans 2 GiB
- * or more, i.e. (tokens - 1) * kv_stride_token * 2 + 256 bytes > 2^31 - 1.
+ * no usable entry yields zeros and lse = -inf.  STEM_ERR_UNSUPPORTED if one sequence of one KV
+ * head spans 2 GiB or more, i.e. (tokens - 1) * kv_stride_token * 2 + 256 bytes > 2^31 - 1.
  */
 int stem_sparse_attn(const stem_shape* shape, const void* q, const void* k, const void* v,
                      const int32_t* counts, const int32_t* indices, int32_t kmax,

@@ -8,6 +8,8 @@
 // ballot prefix compaction: forced blocks, every key above the threshold, and the lowest-indexed
 // keys equal to it until the budget is met.  The result is therefore deterministic and ties go to
 // the lower block index.
+#include <type_traits>
+
 #include "stem_common.h"
 
 namespace stem {
@@ -37,52 +39,49 @@ __device__ __forceinline__ void select_row(Load load, int i, int row_budget, int
     k = min(k, min(i + 1, kmax));
     const int need = max(0, k - forced);               // free blocks to pick, <= nfree
 
-    // groups of 64 candidates beyond the row's free range hold nothing: every loop over the items
-    // skips them (a wave-uniform test), so a short row costs what it holds, not ITEMS
+    // Groups of 64 candidates beyond the row's free range hold nothing.  The loops over the items
+    // run to a compile-time bound N picked per row from a few sizes (a wave-uniform choice), so a
+    // short row costs about what it holds and no loop carries a test per item.
     const int items = (nfree + 63) >> 6;
-    uint32_t key[ITEMS];
-#pragma unroll
-    for (int e = 0; e < ITEMS; ++e) {
-        const int j = fs + e * 64 + lane;
-        key[e] = 0u;                                   // 0 sorts below every real key
-        if (e < items && j < fe) key[e] = ordered_key(load(j));
-    }
-
-    uint32_t tau = 0;
-    int n_eq = 0;                                      // keys equal to tau that are still needed
-    if (need > 0 && need < nfree) {
-        bool exact = false;                            // exactly `need` keys are >= tau
-        for (int bit = 31; bit >= 0 && !exact; --bit) {
-            const uint32_t cand = tau | (1u << bit);
-            int cnt = 0;
-#pragma unroll
-            for (int e = 0; e < ITEMS; ++e)
-                if (e < items) cnt += __popcll(__ballot(key[e] >= cand));
-            if (cnt >= need) tau = cand;
-            exact = cnt == need;
-        }
-        if (exact) {
-            // the keys >= tau are the answer whatever the remaining bits of the k-th largest key
-            // are: express it as "above tau - 1, none equal" (tau >= 1: a bit was just set)
-            tau -= 1;
-        } else {
-            int above = 0;
-#pragma unroll
-            for (int e = 0; e < ITEMS; ++e)
-                if (e < items) above += __popcll(__ballot(key[e] > tau));
-            n_eq = need - above;
-        }
-    }
     const bool take_all = (need >= nfree);
-
-    // emit ascending: forced head, chosen free blocks, forced tail
-    for (int j = lane; j < fs; j += 64) out[j] = j;
     int base = fs;
-    if (need > 0) {
-        int eq_seen = 0;
+    for (int j = lane; j < fs; j += 64) out[j] = j;    // forced head
+    auto run = [&](auto bound) {
+        constexpr int N = decltype(bound)::value;
+        uint32_t key[N];
 #pragma unroll
-        for (int e = 0; e < ITEMS; ++e) {
-            if (e < items) {
+        for (int e = 0; e < N; ++e) {
+            const int j = fs + e * 64 + lane;
+            key[e] = (j < fe) ? ordered_key(load(j)) : 0u; // 0 sorts below every real key
+        }
+        uint32_t tau = 0;
+        int n_eq = 0;                                  // keys equal to tau that are still needed
+        if (need > 0 && need < nfree) {
+            bool exact = false;                        // exactly `need` keys are >= tau
+            for (int bit = 31; bit >= 0 && !exact; --bit) {
+                const uint32_t cand = tau | (1u << bit);
+                int cnt = 0;
+#pragma unroll
+                for (int e = 0; e < N; ++e) cnt += __popcll(__ballot(key[e] >= cand));
+                if (cnt >= need) tau = cand;
+                exact = cnt == need;
+            }
+            if (exact) {
+                // the keys >= tau are the answer whatever the remaining bits of the k-th largest
+                // key are: express it as "above tau - 1, none equal" (tau >= 1: a bit was just set)
+                tau -= 1;
+            } else {
+                int above = 0;
+#pragma unroll
+                for (int e = 0; e < N; ++e) above += __popcll(__ballot(key[e] > tau));
+                n_eq = need - above;
+            }
+        }
+        // chosen free blocks, ascending
+        if (need > 0) {
+            int eq_seen = 0;
+#pragma unroll
+            for (int e = 0; e < N; ++e) {
                 const int j = fs + e * 64 + lane;
                 const bool valid = j < fe;
                 const bool eq = valid && !take_all && key[e] == tau;
@@ -95,7 +94,15 @@ __device__ __forceinline__ void select_row(Load load, int i, int row_budget, int
                 eq_seen += __popcll(eq_mask);
             }
         }
-    }
+    };
+    // bounds: an eighth, a quarter, a half, three quarters of ITEMS, and ITEMS
+    constexpr int kN1 = ITEMS / 8 > 0 ? ITEMS / 8 : 1, kN2 = ITEMS / 4 > 0 ? ITEMS / 4 : 1, kN4 = ITEMS / 2,
+                  kN6 = (3 * ITEMS) / 4;
+    if (items <= kN1) run(std::integral_constant<int, kN1>{});
+    else if (items <= kN2) run(std::integral_constant<int, kN2>{});
+    else if (items <= kN4) run(std::integral_constant<int, kN4>{});
+    else if (items <= kN6) run(std::integral_constant<int, kN6>{});
+    else run(std::integral_constant<int, ITEMS>{});
     const int tail = min(i + 1 - fe, k - base);        // forced tail always fits: k >= forced
     for (int x = lane; x < tail; x += 64) out[base + x] = fe + x;
     for (int x = k + lane; x < kmax; x += 64) out[x] = -1;
