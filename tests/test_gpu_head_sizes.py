@@ -1,6 +1,6 @@
 """Head sizes 64 and 256 through the whole path against the oracle (128 is what every other GPU
-test runs): the pooling, score and fused kernels take the head size as a parameter, the attention
-for these two sizes is a kernel of its own."""
+test runs): the pooling, score and fused kernels take the head size as a parameter, and the attention
+kernel is one template over the block size and the head size, instantiated for all six combinations."""
 import pytest
 
 from paper_2603_06274_amd import workloads as wl
