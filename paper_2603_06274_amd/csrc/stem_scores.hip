@@ -86,37 +86,34 @@ __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
     const float* a_src = q_bar + ((int64_t)h * R + row0) * depth;
     const float* b_src = k_bar + ((int64_t)g * Rk + krow0) * depth;
 
-    // 64 rows x 32 floats per operand and slice = 512 float4: two per thread and operand
-    float4 av[2], bv[2];
-    auto fetch = [&](int kc) {
+    // 64 rows x 32 floats per operand and slice = 512 float4: two per thread and operand.  The
+    // slices are fetched two groups (of two slices) ahead of their use, so at d = 128, S = 1 the
+    // whole contraction is in flight before the first product and the memory latency is paid once
+    // per tile, not once per slice; a group's registers are refilled as soon as it is staged.
+    float4 av[2][2][2], bv[2][2][2];                   // [group parity][slice of the group][part]
+    auto fetch = [&](int kc, float4 (&a)[2], float4 (&b)[2]) {
         // a slice lies inside one residue class a of the query block; its partner is class S-1-a
         const int kb = (S - 1 - (kc >> d_log2)) * d + (kc & (d - 1));
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int idx = tid + kScoreThreads * u;
             const int row = idx >> 3, c4 = (idx & 7) * 4;
-            av[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            bv[u] = av[u];
-            if (i0 + row < n_rows) av[u] = *reinterpret_cast<const float4*>(a_src + (int64_t)(i0 + row) * depth + kc + c4);
-            if (j0 + row < n) bv[u] = *reinterpret_cast<const float4*>(b_src + (int64_t)(j0 + row) * depth + kb + c4);
+            a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            b[u] = a[u];
+            if (i0 + row < n_rows) a[u] = *reinterpret_cast<const float4*>(a_src + (int64_t)(i0 + row) * depth + kc + c4);
+            if (j0 + row < n) b[u] = *reinterpret_cast<const float4*>(b_src + (int64_t)(j0 + row) * depth + kb + c4);
         }
     };
-    auto stage = [&](int buf) {
+    auto stage = [&](int buf, const float4 (&a)[2], const float4 (&b)[2]) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int idx = tid + kScoreThreads * u;
             const int row = idx >> 3, c4 = (idx & 7) * 4;
-            *reinterpret_cast<float4*>(&a_s[buf][row][c4]) = av[u];
-            *reinterpret_cast<float4*>(&b_s[buf][row][c4]) = bv[u];
+            *reinterpret_cast<float4*>(&a_s[buf][row][c4]) = a[u];
+            *reinterpret_cast<float4*>(&b_s[buf][row][c4]) = b[u];
         }
     };
-    fetch(0);
-    stage(0);
-    __syncthreads();
-    int buf = 0;
-    for (int kc = 0; kc < depth; kc += kChunk, buf ^= 1) {
-        const bool more = kc + kChunk < depth;
-        if (more) fetch(kc + kChunk);
+    auto products = [&](int buf) {
 #pragma unroll
         for (int u = 0; u < kChunk / 8; ++u) {
             const float4 a = *reinterpret_cast<const float4*>(&a_s[buf][wi + col][u * 8 + hi * 4]);
@@ -126,9 +123,32 @@ __global__ __launch_bounds__(kScoreThreads) void block_scores_kernel(
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
         }
-        // the other buffer was last read before the previous barrier
-        if (more) stage(buf ^ 1);
+    };
+    // depth is a multiple of 64 (head sizes 64, 128, 256 times S): groups of two slices
+    const int groups = depth / (2 * kChunk);
+    auto fetch_group = [&](int g, int par) {
+        fetch(g * 2 * kChunk, av[par][0], bv[par][0]);
+        fetch(g * 2 * kChunk + kChunk, av[par][1], bv[par][1]);
+    };
+    fetch_group(0, 0);
+    if (groups > 1) fetch_group(1, 1);
+    stage(0, av[0][0], bv[0][0]);
+    __syncthreads();
+    // one group: slice 0 sits in LDS buffer 0; every barrier separates the last read of a buffer from
+    // its next write (the buffer staged during a slice's products was last read before the previous barrier)
+    auto one_group = [&](int g, int par) {
+        stage(1, av[par][1], bv[par][1]);              // the group's second slice
+        products(0);
         __syncthreads();
+        const bool more = g + 1 < groups;
+        if (more) stage(0, av[par ^ 1][0], bv[par ^ 1][0]);   // the next group's first slice
+        if (g + 2 < groups) fetch_group(g + 2, par);   // this group's registers are free again
+        products(1);
+        __syncthreads();
+    };
+    for (int g = 0; g < groups; g += 2) {
+        one_group(g, 0);
+        if (g + 1 < groups) one_group(g + 1, 1);
     }
 
     // accumulator v of a lane: column wj + col, row wi + 8*(v/4) + 4*hi + v%4
