@@ -153,6 +153,10 @@ def test_fused_estimate_select_128k_and_most_blocks():
         pf.run(fused=False)
         torch.cuda.synchronize()
         agree = (fused_idx == pf.indices).all(dim=2) & (fused_counts == pf.counts)      # [Hq, R]
+        # the two entry points may resolve near-ties of the fp32 metric differently (rounding order of
+        # the score sums): counted here, and bounded
+        say("%s: %d of %d rows get different lists from the fused and the unfused entry point"
+            % (w.name, int((~agree).sum().item()), agree.numel()))
         assert agree.float().mean().item() > 0.99
         B = w.block_size
         for (lo, hi, nb, row0) in so.sequence_table(w.cu_seqlens, B):
