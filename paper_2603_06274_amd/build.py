@@ -43,10 +43,33 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
+def check_wait_states(extra=()) -> None:
+    """The attention kernel places some matrix instructions (and the wait states they need) by hand:
+    compile it to assembly once more and verify the distances in what the compiler made of it."""
+    from . import wait_states
+    asm_path = os.path.join(OBJ, "stem_attn.s")
+    cmd = [hipcc(), *COMMON, *extra, "--cuda-device-only", "-S", "-x", "hip", os.path.join(CSRC, "stem_attn.hip"),
+           "-o", asm_path]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc -S failed for stem_attn.hip:\n%s\n%s" % (res.stdout, res.stderr))
+    with open(asm_path) as f:
+        asm = f.read()
+    names = wait_states.kernels(asm, "sparse_attn_kernel")
+    if len(names) < 6:
+        raise RuntimeError("expected the six attention kernels in %s, found %d" % (asm_path, len(names)))
+    for name in names:
+        broken = wait_states.check_kernel(asm, name)
+        if broken:
+            raise RuntimeError("wait states missing in %s:\n  %s" % (name, "\n  ".join(broken[:20])))
+
+
 def build(extra_flags=(), verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + 1)) as ex:
+        checked = ex.submit(check_wait_states, list(extra_flags))
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
+        checked.result()
     cmd = [hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", LIB]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:

@@ -91,6 +91,61 @@ __device__ __forceinline__ void wait_lgkmcnt(int n) {   // n is a constant after
 // matrix instructions that consume the current group.
 #define STEM_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// Matrix instructions with the register file chosen by hand (head size 256).  A wave that may use
+// more than 256 registers has them in two halves: vector registers, which every instruction can
+// use, and accumulator registers, which only matrix instructions (and copies) can.  Left to itself
+// the compiler then puts the results of ALL matrix instructions of a function into accumulator
+// registers, also the S^T scores that the softmax has to read with vector instructions, and copies
+// them back and forth (about 400 copies per block at d = 256).  Written as inline assembly the
+// placement is ours: S^T results in vector registers, the O^T accumulators and the Q operands in
+// accumulator registers, no copy in the loop.  The price: the compiler no longer knows these are
+// matrix instructions, so the wait states it would insert are placed by hand where the instruction
+// order does not already guarantee them (kManualHazards sites below): 12 issue slots between a
+// 32x32x16 product and a vector access to its result, 5 after a 4x4x4 one, 2 between a vector
+// write and a matrix instruction that reads it.  The build checks the finished assembly for these
+// distances (wait_states.py), since register allocation may add copies the source does not show.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4_t as_u32x4(uint4 x) { return u32x4_t{x.x, x.y, x.z, x.w}; }
+__device__ __forceinline__ void mfma_scores_first(f32x16_t& d, uint4 a, const u32x4_t& b) {
+    // (early clobber: the result registers must not be the ones an operand is still read from)
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(as_u32x4(a)), "a"(b));
+}
+__device__ __forceinline__ void mfma_scores(f32x16_t& d, uint4 a, const u32x4_t& b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(as_u32x4(a)), "a"(b));
+}
+__device__ __forceinline__ void mfma_output(f32x16_t& d, uint4 a, uint4 b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(as_u32x4(a)), "v"(as_u32x4(b)));
+}
+// the first product into an O^T tile: nothing to add to, so no zero has to be written beforehand
+__device__ __forceinline__ void mfma_output_first(f32x16_t& d, uint4 a, uint4 b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=a"(d) : "v"(as_u32x4(a)), "v"(as_u32x4(b)));
+}
+// Pins a Q operand to accumulator registers where it is loaded.  (Given only the "a" constraint at
+// its uses, the compiler copies it there right before each use, and a matrix instruction may read
+// a register a vector instruction has written only two issue slots later.)
+__device__ __forceinline__ void pin_to_acc(u32x4_t& x) { asm volatile("" : "+a"(x)); }
+// the row-sum product; its B operand has just been written by a vector instruction (2 wait states)
+__device__ __forceinline__ void mfma_row_sum(f32x4_t& d, uint2 ones, uint2 four) {
+    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+    asm volatile("s_nop 1\n\tv_mfma_f32_4x4x4_16b_bf16 %0, %1, %2, %0"
+                 : "+v"(d)
+                 : "v"(u32x2_t{ones.x, ones.y}), "v"(u32x2_t{four.x, four.y}));
+}
+// Idle issue slots (4 cycles each): what separates a matrix instruction's write from a dependent
+// vector access when nothing else does.  Each form names the registers it protects as operands it
+// "modifies": only that data dependence keeps the compiler from moving the dependent instructions
+// to the other side of the wait.
+template <int N, typename R>
+__device__ __forceinline__ void wait_states_v(R& r) {  // r: a result in vector registers
+    asm volatile("s_nop %1" : "+v"(r) : "n"(N - 1));
+}
+template <int N>
+__device__ __forceinline__ void wait_states_acc(f32x16_t (&o)[8]) {   // o: the O^T accumulators
+    asm volatile("s_nop %8"
+                 : "+a"(o[0]), "+a"(o[1]), "+a"(o[2]), "+a"(o[3]), "+a"(o[4]), "+a"(o[5]), "+a"(o[6]), "+a"(o[7])
+                 : "n"(N - 1));
+}
+
 // One 1 KiB slice (1024 / 2D rows) of a B x D bf16 block, global -> LDS.  A block is D / 16 slices
 // per wave: wave w issues slices u*NW + w, so that the row's swizzle term depends on u with a short
 // period only (1, 2 or 4).  Requests are issued one at a time between matrix
@@ -145,8 +200,12 @@ struct SoftmaxSchedule {
     // O^T reaches the last tile (its pairs issued, all others consumed).
     static constexpr int check_slot(int c) { return c == 0 ? NS : NS + KS * (KT - 1); }
     // slot after whose matrix instruction pair q is issued: the eight pairs of tile t are spread over
-    // the KS slots that follow the tile's completion
-    static constexpr int issue_slot(int q) { return (q / 8 + 1) * KS + ((q % 8) * KS) / 8; }
+    // the KS slots that follow the tile's completion.  At d = 256, where the matrix instructions are
+    // placed by hand, a tile's first pair keeps kLead + 1 matrix instructions (and the operand wait of
+    // every second one) between itself and the instruction that completed the tile: the 12 issue
+    // slots after which that instruction's result may be read by a vector instruction.
+    static constexpr int kLead = KS == 16 ? 7 : 0;
+    static constexpr int issue_slot(int q) { return (q / 8 + 1) * KS + kLead + ((q % 8) * (KS - kLead)) / 8; }
     // slot of the O^T instruction that first consumes pair q
     static constexpr int use_slot(int q) { return NS + DT * (2 * (q / 8) + (q % 8) / 4); }
     // pairs issued once slot `slot` is issued
@@ -209,6 +268,8 @@ __device__ __forceinline__ void sparse_attn_body(
     constexpr int NW = B / 32;                         // waves
     constexpr int kRowBytes = D * 2;                   // one K or V row in LDS
     constexpr int kSliceRows = 1024 / kRowBytes;       // rows one wave-wide 1 KiB request covers
+    // head size 256 needs more than 256 registers per lane: matrix instructions by hand (see above)
+    constexpr bool kManualHazards = D == 256;
     // LDS swizzles, as XORs on the 16-byte chunk index of a row: K spreads the 16 rows a quarter-wave
     // reads one chunk of over all banks, V the 4 rows x 32 bytes of a transposing read (at d = 64 two
     // 128-byte rows share the 64 banks, so the row's bit 0 does the spreading by itself)
@@ -311,6 +372,7 @@ __device__ __forceinline__ void sparse_attn_body(
 
     // ---- Q rows of this wave as B operands: KS k-steps of 16 along d ----
     bf16x8_t q_reg[KS];
+    u32x4_t q_acc[kManualHazards ? KS : 1];            // the same, for the hand-placed form
     {
         const uint16_t* src = q + (int64_t)tok_q * q_st + (int64_t)h * q_sh + hi * 8;
 #pragma unroll
@@ -318,6 +380,10 @@ __device__ __forceinline__ void sparse_attn_body(
             uint4 x = make_uint4(0u, 0u, 0u, 0u);
             if (q_valid) x = *reinterpret_cast<const uint4*>(src + ks * 16);
             q_reg[ks] = as_bf16x8(x);
+            if constexpr (kManualHazards) {
+                q_acc[ks] = as_u32x4(x);
+                pin_to_acc(q_acc[ks]);
+            }
         }
     }
 
@@ -382,6 +448,12 @@ __device__ __forceinline__ void sparse_attn_body(
     // every lane gets the sum of its own four values, in each of its four result registers.
     auto softmax_pair = [&](int q) {
         const int t = q >> 3, x = (q & 7) * 2;
+        // hand-placed form: a matrix result may be read 12 issue slots after its instruction; the
+        // schedule keeps that many instructions in between (kLead), two more for margin
+        if constexpr (kManualHazards) {
+            static_assert(!kManualHazards || Sched::kLead + 1 + (Sched::kLead + 1) / 2 >= 12, "S^T -> softmax distance");
+            if ((q & 7) == 0) wait_states_v<2>(s_acc[t]);
+        }
         const float p0 = __builtin_amdgcn_exp2f(s_acc[t][x] * sl2 - off);
         const float p1 = __builtin_amdgcn_exp2f(s_acc[t][x + 1] * sl2 - off);
         uint32_t pk = pack_bf16(p0, p1);
@@ -393,15 +465,21 @@ __device__ __forceinline__ void sparse_attn_body(
         if (q & 1) {                                   // windows hold an even number of pairs
             const uint2 four = make_uint2(p_pk[t][(q & 7) - 1], pk);
             const uint2 ones = make_uint2(0x3f803f80u, 0x3f803f80u);
-            l_win = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(s16x4_t, ones),
-                                                           __builtin_bit_cast(s16x4_t, four), l_win, 0, 0, 0);
+            if constexpr (kManualHazards)
+                mfma_row_sum(l_win, ones, four);
+            else
+                l_win = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(s16x4_t, ones),
+                                                               __builtin_bit_cast(s16x4_t, four), l_win, 0, 0, 0);
         }
     };
     auto softmax_slot = [&](int slot) {                // one pair per slot at most (two at d = 64)
 #pragma unroll
         for (int q = pairs_by(slot - 1); q < pairs_by(slot); ++q) softmax_pair(q);
     };
-    auto window_sum = [&]() { return l_win[0]; };
+    auto window_sum = [&]() {
+        if constexpr (kManualHazards) wait_states_v<6>(l_win);   // after the window's last row-sum product
+        return l_win[0];
+    };
     auto clear_sum = [&]() { l_win = f32x4_t{0.f, 0.f, 0.f, 0.f}; };
     // exp2-domain offset of the reference; a query that has seen nothing yet (m_ref = -inf) uses 0,
     // which keeps its masked scores at exp2(-inf) = 0
@@ -423,10 +501,12 @@ __device__ __forceinline__ void sparse_attn_body(
             const float corr = (m_ref == neg_inf) ? 0.f : __builtin_amdgcn_exp2f((m_ref - mx) * sl2);
             m_ref = mx;
             l_run *= corr;
+            if constexpr (kManualHazards) wait_states_acc<16>(o_acc);   // the last O^T instruction has written
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                 for (int x = 0; x < 16; ++x) o_acc[dt][x] *= corr;
+            if constexpr (kManualHazards) wait_states_acc<4>(o_acc);    // before the next one reads them
         }
         off = reference_offset();
         clear_sum();
@@ -469,6 +549,7 @@ __device__ __forceinline__ void sparse_attn_body(
     };
     // accumulator x of tile t is key t*32 + 16*(x/8) + 8*hi + x%8 of the block
     auto mask_tile = [&](int t, int limit) {
+        if constexpr (kManualHazards) wait_states_v<16>(s_acc[t]);   // the tile's last matrix instruction has written
 #pragma unroll
         for (int x = 0; x < 16; ++x)
             if (t * 32 + 16 * (x >> 3) + (x & 7) > limit) s_acc[t][x] = neg_inf;
@@ -512,8 +593,13 @@ __device__ __forceinline__ void sparse_attn_body(
                 }
                 if (n < NS / 2 && n % kStepsPerRequestV == 0)
                     v_rq.issue(n / kStepsPerRequestV, v_slice0, slice_step, slice_lds_step);
-                s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[n % kSlots]), q_reg[n % KS],
-                                                                  (n % KS) == 0 ? zero16 : s_acc[t], 0, 0, 0);
+                if constexpr (kManualHazards) {
+                    if ((n % KS) == 0) mfma_scores_first(s_acc[t], ka[n % kSlots], q_acc[n % KS]);
+                    else mfma_scores(s_acc[t], ka[n % kSlots], q_acc[n % KS]);
+                } else {
+                    s_acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka[n % kSlots]), q_reg[n % KS],
+                                                                      (n % KS) == 0 ? zero16 : s_acc[t], 0, 0, 0);
+                }
                 if constexpr (!kFirst) softmax_slot(n);
                 STEM_SCHED_FENCE();
             }
@@ -542,8 +628,12 @@ __device__ __forceinline__ void sparse_attn_body(
                 if (n % kStepsPerRequestK == 1) k_rq.issue(n / kStepsPerRequestK, k_slice0, slice_step, slice_lds_step);
                 const int g2 = n / DT, t = g2 >> 1, u = g2 & 1, dt = n % DT;
                 const uint4 pb = make_uint4(p_pk[t][u * 4], p_pk[t][u * 4 + 1], p_pk[t][u * 4 + 2], p_pk[t][u * 4 + 3]);
-                o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[n % kSlots]), as_bf16x8(pb),
-                                                                   o_acc[dt], 0, 0, 0);
+                if constexpr (kManualHazards) {
+                    if (kFirst && n < DT) mfma_output_first(o_acc[dt], va[n % kSlots], pb);
+                    else mfma_output(o_acc[dt], va[n % kSlots], pb);
+                } else
+                    o_acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(va[n % kSlots]), as_bf16x8(pb),
+                                                                       o_acc[dt], 0, 0, 0);
                 softmax_slot(NS + n);
                 STEM_SCHED_FENCE();
             }
@@ -558,6 +648,7 @@ __device__ __forceinline__ void sparse_attn_body(
     if (cnt > 0) one_block(0, std::true_type{});
     for (int it = 1; it < cnt; ++it) one_block(it, std::false_type{});
     STEM_WAIT_VMCNT(0);                                // no request may outlive the workgroup's LDS
+    if constexpr (kManualHazards) wait_states_acc<16>(o_acc);   // the last O^T instructions have written
 
     // ---- normalise and store: accumulator x of d tile dt is column dt*32 + 8*(x/4) + 4*hi + x%4 ----
     float l_tot;
