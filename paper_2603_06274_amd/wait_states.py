@@ -18,8 +18,8 @@ Rules checked (wait states = instructions issued in between, `s_nop N` counting 
   * a matrix instruction may read a register 2 wait states after a vector instruction wrote it.
 
 The scan is linear over the function.  At each branch the instructions at the target are scanned
-as well (24 wait states deep) with the state at the branch; after an unconditional branch or the
-end of the program the state is dropped.
+as well with the state at the branch, 24 wait states deep in total and through up to three further
+branches; after an unconditional branch or the end of the program the state is dropped.
 """
 from __future__ import annotations
 
@@ -29,6 +29,7 @@ from typing import Dict, List, Tuple
 _REG = re.compile(r"\b([va])(?:\[(\d+):(\d+)\]|(\d+)\b)")
 _LABEL = re.compile(r"^(\.LBB\d+_\d+):")
 LOOKAHEAD = 24
+MAX_BRANCH_DEPTH = 4
 
 
 def _regs(text: str) -> set:
@@ -54,8 +55,8 @@ def check_kernel(asm: str, symbol: str) -> List[str]:
     labels = {m.group(1): i for i in range(start, end) for m in [_LABEL.match(src[i])] if m}
     found = set()
 
-    def scan(i: int, pending: List[Tuple], written: Dict, state: int, nested: bool) -> None:
-        first = state
+    def scan(i: int, pending: List[Tuple], written: Dict, state: int, depth: int, first: int) -> None:
+        nested = depth > 0
         while i < end:
             line = src[i].split(";")[0].strip()
             i += 1
@@ -69,8 +70,8 @@ def check_kernel(asm: str, symbol: str) -> List[str]:
                 state += int(args) + 1
                 continue
             if op == "s_branch" or op.startswith("s_cbranch"):
-                if not nested and args in labels:
-                    scan(labels[args], list(pending), dict(written), state + 1, True)
+                if depth < MAX_BRANCH_DEPTH and args in labels:
+                    scan(labels[args], list(pending), dict(written), state + 1, depth + 1, first if nested else state + 1)
                 state += 1
                 if op == "s_branch":
                     if nested:
@@ -126,5 +127,5 @@ def check_kernel(asm: str, symbol: str) -> List[str]:
             for r in [r for r, w in written.items() if state - w[0] >= 4]:
                 del written[r]
 
-    scan(start + 1, [], {}, 0, False)
+    scan(start + 1, [], {}, 0, 0, 0)
     return sorted(found)

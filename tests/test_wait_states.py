@@ -63,6 +63,10 @@ def test_branch_targets_are_followed():
     read = "\tv_mul_f32_e32 v30, v31, v7\n"
     body = S_TILE + "\ts_cbranch_scc0 .LBB0_2\n" + FILLER * 12 + "\ts_branch .LBB0_3\n.LBB0_2:\n" + read + ".LBB0_3:\n"
     assert broken(body)
+    # a second branch on the way
+    body = (S_TILE + "\ts_cbranch_scc0 .LBB0_2\n" + FILLER * 12 + "\ts_branch .LBB0_4\n.LBB0_2:\n" + FILLER * 2 +
+            "\ts_cbranch_scc1 .LBB0_3\n" + FILLER * 12 + "\ts_branch .LBB0_4\n.LBB0_3:\n" + read + ".LBB0_4:\n")
+    assert broken(body)
     # after an unconditional branch nothing falls through
     assert not broken(S_TILE + "\ts_branch .LBB0_3\n.LBB0_2:\n" + read + ".LBB0_3:\n" + FILLER * 12)
 
