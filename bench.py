@@ -125,6 +125,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size dispatch the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings are scaled by")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="after the timed steps, also time the vendor library's dense bf16 GEMM (16384^3, "
+                         "torch.matmul) in the same process: what dense matrix work sustains on this box")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is a one-GPU hot path (no collectives, no sharding); run with --gpus 1")
@@ -246,6 +249,16 @@ def main():
                                     "unit": "GB/s", "frac": round(est_gbs / PEAK_HBM_GBS, 4),
                                     "algorithmic_bytes": est_bytes},
     }
+    if args.vendor_gemm:                               # context for the roofline fraction, not part of the path
+        n = 16384
+        a = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
+        b = torch.randn(n, n, device=dev, dtype=torch.bfloat16)
+        c = torch.empty(n, n, device=dev, dtype=torch.bfloat16)
+        t_gemm = time_call(lambda: torch.matmul(a, b, out=c), n=20)
+        result["vendor_gemm"] = {"what": "torch.matmul, bf16, 16384^3, random normal data", "ms": round(t_gemm, 4),
+                                 "tflops": round(2.0 * n ** 3 / (t_gemm * 1e-3) / 1e12, 1),
+                                 "attention_over_gemm": round(attn_tflops / (2.0 * n ** 3 / (t_gemm * 1e-3) / 1e12), 4)}
+        del a, b, c
     if not args.no_cpu_baseline and default_options:   # the oracle leg times the default path only
         result["cpu_baseline"] = cpu_baseline(w, data, dense_flops, pf.counts.cpu().numpy(), pf.indices.cpu().numpy())
     print(json.dumps(result), flush=True)
