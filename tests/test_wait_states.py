@@ -31,6 +31,9 @@ def test_accumulation_follows_at_once_but_a_shifted_result_does_not():
     assert not broken(S_TILE + S_TILE)
     shifted = "\tv_mfma_f32_32x32x16_bf16 v[8:23], v[24:27], a[0:3], v[8:23]\n"
     assert broken(S_TILE + FILLER * 9 + shifted)
+    assert not broken(S_TILE + FILLER * 10 + shifted)
+    # results that overlap without a read in between are ordered by the pipe itself
+    assert not broken(S_TILE + "\tv_mfma_f32_32x32x16_bf16 v[8:23], v[24:27], a[0:3], 0\n")
     as_operand = "\tv_mfma_f32_32x32x16_bf16 v[48:63], v[0:3], a[0:3], v[48:63]\n"
     assert broken(S_TILE + FILLER * 11 + as_operand)
     assert not broken(S_TILE + FILLER * 12 + as_operand)
