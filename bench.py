@@ -195,7 +195,7 @@ def main():
     attn_tflops = attn_flops / (t_attn_avg * 1e-3) / 1e12
 
     # the two kernels of stage 1, timed on their own (outside the timed region above)
-    def time_call(fn, n=10):
+    def time_call(fn, n=15):
         fn()
         torch.cuda.synchronize()
         pairs = []
@@ -206,7 +206,7 @@ def main():
             b.record()
             pairs.append((a, b))
         torch.cuda.synchronize()
-        return sum(a.elapsed_time(b) for a, b in pairs) / n
+        return median([a.elapsed_time(b) for a, b in pairs])
 
     t_pool = time_call(pf.pool)
     t_scores = time_call(pf.block_scores)
